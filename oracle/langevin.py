@@ -1,0 +1,130 @@
+"""ORACLE (test infrastructure only) -- speculative sampling for unadjusted Langevin, in fp64.
+
+Follows Alg. "Speculative Sampling for Unadjusted Langevin Diffusion" (App. on Langevin
+diffusions) step by step, vectorised over independent chains only:
+
+    target   X_{k+1} = X_k - gamma grad E(X_k)     + sqrt(2 gamma) W_k
+    draft    X_{k+1} = X_k - gamma grad E^(X_k)    + sqrt(2 gamma) W_k
+    Delta_{k-1} = sqrt(gamma/2) (grad E(Y~_{k-1}) - grad E^(Y~_{k-1})),  e = Delta/|Delta|
+    accept iff U <= min(1, N(Z + Delta; 0, I) / N(Z; 0, I)),  Z = the noise that drew Y~_k
+    on reject  Y_k = Y~_{k-1} - gamma grad E(Y~_{k-1}) + sqrt(2 gamma) (I - 2 e e^T) Z
+
+(the listing's reject branch prints "gamma E": read as gamma grad E, as in the target update).
+The proxy is either a cheaper gradient or the frozen one, grad E^(x_{n+j}) = grad E(x_n).
+
+This is written independently of oracle/speculative.py on purpose: the two formulations are
+pinned to each other in tests/test_oracle_langevin.py (the ULA chain is the general Gaussian
+chain with a = 1, c = -gamma, sigma = sqrt(2 gamma), D = grad E), and to the stationary
+variance of ULA on a quadratic energy.
+"""
+from __future__ import annotations
+
+from typing import Callable, Optional
+
+import numpy as np
+
+from . import philox
+
+Grad = Callable[[np.ndarray], np.ndarray]
+
+
+def ula_window(gradE: Grad, x, n, chain_id, K: int, T: int, gamma: float, seed: int,
+               grad_proxy: Optional[Grad] = None):
+    """One window for every chain.  Returns (x_out [B,d], adv [B], rejected [B],
+    logratio [B,K], logu [B,K]).  ``grad_proxy`` None = frozen gradient."""
+    x = np.asarray(x, dtype=np.float64)
+    n = np.asarray(n)
+    B, d = x.shape
+    Kt = np.minimum(K, T - n)
+    sq2g = np.sqrt(2.0 * gamma)
+    g_start = gradE(x)
+    # -- draft states, sequentially, remembering the noise that drew them
+    Ytil = np.zeros((B, K + 1, d))
+    Ytil[:, 0] = x
+    Z = np.zeros((B, K, d))
+    Ghat = np.zeros((B, K, d))
+    for j in range(1, K + 1):
+        act = np.nonzero(j <= Kt)[0]
+        if act.size == 0:
+            break
+        gh = g_start[act] if grad_proxy is None else grad_proxy(Ytil[act, j - 1])
+        z = philox.normals(seed, chain_id[act], n[act] + j, d)
+        Ytil[act, j] = Ytil[act, j - 1] - gamma * gh + sq2g * z
+        Z[act, j - 1] = z
+        Ghat[act, j - 1] = gh
+    # -- in parallel: grad E at Y~_n .. Y~_{n_L - 1}
+    G = np.zeros((B, K, d))
+    G[:, 0] = g_start
+    for j in range(2, K + 1):
+        act = np.nonzero(j <= Kt)[0]
+        if act.size:
+            G[act, j - 1] = gradE(Ytil[act, j - 1])
+    # -- sequential accept / reject
+    x_out = np.zeros((B, d))
+    adv = np.zeros(B, dtype=np.int32)
+    rejected = np.zeros(B, dtype=bool)
+    logratio = np.zeros((B, K))
+    logu = np.zeros((B, K))
+    running = np.ones(B, dtype=bool)
+    for j in range(1, K + 1):
+        act = np.nonzero(j <= Kt)[0]
+        if act.size == 0:
+            break
+        Delta = np.sqrt(gamma / 2.0) * (G[act, j - 1] - Ghat[act, j - 1])
+        z = Z[act, j - 1]
+        zd = np.sum(z * Delta, axis=1)
+        dd = np.sum(Delta * Delta, axis=1)
+        lr = -zd - 0.5 * dd                                   # log N(Z+Delta) - log N(Z)
+        lu = np.log(philox.uniforms(seed, chain_id[act], n[act] + j))
+        acc = (dd == 0.0) | (lu <= np.minimum(0.0, lr))
+        with np.errstate(divide="ignore", invalid="ignore"):
+            coef = np.where(dd > 0.0, zd / dd, 0.0)
+        refl = (Ytil[act, j - 1] - gamma * G[act, j - 1]
+                + sq2g * (z - 2.0 * coef[:, None] * Delta))
+        Y = np.where(acc[:, None], Ytil[act, j], refl)
+        logratio[act, j - 1] = lr
+        logu[act, j - 1] = lu
+        live = running[act]
+        upd = act[live]
+        x_out[upd] = Y[live]
+        adv[upd] = j
+        rej_now = act[live & ~acc]
+        rejected[rej_now] = True
+        running[rej_now] = False
+    return x_out, adv, rejected, logratio, logu
+
+
+def ula_sample(gradE: Grad, B: int, d: int, K: int, T: int, gamma: float, seed: int,
+               grad_proxy: Optional[Grad] = None, chain_ids: Optional[np.ndarray] = None):
+    """Whole algorithm; X_0 ~ N(0, Id) from the keyed initial stream ("Set Y_0 arbitrarily").
+    Returns (X_T in the order of chain_ids, total windows over chains, total rejections)."""
+    ids0 = np.arange(B, dtype=np.int64) if chain_ids is None else np.asarray(chain_ids, dtype=np.int64)
+    ids = ids0.copy()
+    pos = np.arange(ids.shape[0])
+    x = philox.initial_state(seed, ids, d)
+    n = np.zeros(ids.shape[0], dtype=np.int64)
+    out = np.zeros((ids.shape[0], d))
+    chain_windows = 0
+    rejections = 0
+    while n.size:
+        x_out, adv, rej, _, _ = ula_window(gradE, x, n, ids, K, T, gamma, seed, grad_proxy)
+        chain_windows += n.size
+        rejections += int(rej.sum())
+        n = n + adv
+        done = n >= T
+        out[pos[done]] = x_out[done]
+        keep = ~done
+        x, n, ids, pos = x_out[keep], n[keep], ids[keep], pos[keep]
+    return out, chain_windows, rejections
+
+
+def ula_sequential(gradE: Grad, B: int, d: int, T: int, gamma: float, seed: int,
+                   chain_ids: Optional[np.ndarray] = None):
+    """Plain ULA with the same keyed noise."""
+    ids = np.arange(B, dtype=np.int64) if chain_ids is None else np.asarray(chain_ids, dtype=np.int64)
+    x = philox.initial_state(seed, ids, d)
+    sq2g = np.sqrt(2.0 * gamma)
+    for k in range(T):
+        z = philox.normals(seed, ids, np.full(ids.shape[0], k + 1), d)
+        x = x - gamma * gradE(x) + sq2g * z
+    return x
