@@ -1,0 +1,153 @@
+/* sd.h -- C ABI of the speculative-sampling hot path for diffusion chains on MI355X (gfx950).
+ *
+ * One window of the method (paper: Alg. "Speculative Sampling for DDM" and its detailed form in
+ * App. "Detailed implementation of speculative sampling for diffusion models"):
+ *
+ *     D0 = D(y_n, n)                         target prediction at the window start (caller, sdden.h)
+ *     sd_draft   : y~_{n+1..n+Kt} from the frozen draft mean  a_k y~_k + c_k D0      (Sec. 3.1)
+ *     Dq_j = D(y~_{n+j-1}, n+j-1)            one batched target call on the drafts  (caller)
+ *     sd_verify  : accept test, first rejection, reflection-maximal-coupling resample (Sec. 3.3)
+ *     sd_advance : n <- n + advance, finished chains leave the batch                 ("Set n <- k")
+ *     sd_langevin_window : the whole window for unadjusted Langevin on a Gaussian-mixture energy,
+ *                  fused in one launch (Sec. 5 and App. on Langevin diffusions)
+ *
+ * Notation: T = chain length (the paper's K), K = window length (the paper's L),
+ * Kt = min(K, T - n) (the paper's L-tilde), B = chains in the batch, d = state dimension.
+ * The chain is the Gaussian autoregression
+ *     y_{k+1} ~ N( a[k] * y_k + c[k] * D(y_k, k),  sigma[k]^2 I ),   k = 0 .. T-1,
+ * which covers the paper's Euler-Maruyama chain (a = 1, c = gamma, D = b^q), the DDPM ancestral
+ * sampler with an x0-predicting network, and ULA (a = 1, c = -gamma, D = grad E, sigma = sqrt(2 gamma)).
+ *
+ * Conventions
+ *  - Every pointer argument marked "dev" is DEVICE memory owned by the caller; "host" is host memory.
+ *    Row-major everywhere; [B,K,d] keeps the K rows of one chain adjacent.  Buffers must not
+ *    overlap unless a call says "in place".
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  The four window calls
+ *    only enqueue kernels: no allocation, no host synchronisation, no use of another stream.
+ *  - Return value: SD_OK or a negative sd_status.  Arguments are validated on the host before
+ *    anything is enqueued; nothing is enqueued on error.  sd_last_error() gives the text.
+ *  - Random numbers: Philox4x32-10 keyed by (seed; chain_id, state index k, stream, block), so a
+ *    result depends on the chain's id and step only -- never on B, on the order of chains, or on
+ *    how a run is split into calls.  Stream 0: noise that produces state k; stream 1: uniform
+ *    that tests state k; stream 2: initial state.  32-bit word w -> u = ((w>>9)+1/2) 2^-23;
+ *    normals by Box-Muller on word pairs (0,1) and (2,3) of a block (= 4 consecutive elements).
+ *  - Accept iff  log u <= min(0, (-Z.Delta - |Delta|^2/2) / tau)  evaluated in fp64, where
+ *    Delta = (m^p - m^q)/sigma and Z = (y~ - m^p)/sigma is recomputed from the stored draft.
+ *    |Delta| = 0 accepts without reflection.
+ */
+#ifndef SD_H
+#define SD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SD_OK = 0,
+  SD_ERR_ARG = -1,        /* null pointer, non-positive size, K > SD_MAX_WINDOW, misuse            */
+  SD_ERR_SCHEDULE = -2,   /* sigma <= 0 or a non-finite coefficient                               */
+  SD_ERR_WORKSPACE = -3,  /* workspace missing or too small for this B                            */
+  SD_ERR_HIP = -4,        /* a HIP runtime call failed (text in sd_last_error)                    */
+  SD_ERR_UNSUPPORTED = -5 /* shape outside what the kernels were built for (text says which)      */
+} sd_status;
+
+#define SD_MAX_WINDOW 64          /* K <= 64: one wavefront ballot resolves the first rejection   */
+
+#define SD_DRAFT_FROZEN 0         /* draft mean a y~ + c D0, D0 fixed over the window (Sec. 3.1)   */
+#define SD_DRAFT_EXPLICIT 1       /* caller supplies the draft means mp[B,K,d] (any drafter)       */
+
+typedef struct sd_ctx sd_ctx;     /* opaque; owns only its device copy of the schedule            */
+
+/* Host arrays of length T, copied at sd_create. */
+typedef struct {
+  int32_t T;
+  const float* a;
+  const float* c;
+  const float* sigma;             /* > 0: Delta divides by it                                     */
+} sd_schedule;
+
+/* Create a context for chains of dimension d and window K on the current HIP device.
+ * Allocates and fills the device schedule (the only allocation the library ever makes for the
+ * window calls).  Errors: SD_ERR_ARG, SD_ERR_SCHEDULE, SD_ERR_HIP. */
+int sd_create(const sd_schedule* schedule, int32_t d, int32_t K, sd_ctx** out);
+int sd_destroy(sd_ctx* ctx);
+
+int sd_set_seed(sd_ctx* ctx, uint64_t seed);            /* default 0                              */
+int sd_set_draft_mode(sd_ctx* ctx, int mode);           /* SD_DRAFT_FROZEN (default) / _EXPLICIT  */
+/* Temperature tau > 0 of the accept test (App. "Influence of the temperature"); 1 = exact.       */
+int sd_set_temperature(sd_ctx* ctx, float tau);
+/* Optional device-resident batch size.  When set (non-NULL, dev int32), every window call treats
+ * only the first min(B, *count) chains as present, so a fixed launch sequence (for instance a
+ * captured HIP graph) keeps working while sd_advance shrinks the batch.  NULL restores B.        */
+int sd_set_active_count(sd_ctx* ctx, const int32_t* count);
+
+/* Scratch for sd_advance (compaction map): bytes needed for batches up to Bmax, and the buffer. */
+size_t sd_workspace_bytes(const sd_ctx* ctx, int32_t Bmax);
+int sd_set_workspace(sd_ctx* ctx, void* workspace /*dev*/, size_t bytes);
+
+/* Y_0 ~ N(0, Id), n = 0 ("Sample Y_0 ~ N(0, Id) and set n = 0").
+ * chain_id [B] dev (in), y [B,d] dev (out), n [B] dev (out). */
+int sd_init_state(sd_ctx* ctx, int32_t B, const int64_t* chain_id, float* y, int32_t* n,
+                  void* stream);
+
+/* Frozen draft rollout (eq. "frozen draft model"; detailed algorithm, first for-loop):
+ *   y~_{k+1} = a[k] y~_k + c[k] D0 + sigma[k] z_{k+1},  k = n .. n+Kt-1,  y~_n = y.
+ * in : y [B,d], n [B], chain_id [B], D0 [B,d] = D(y, n)                               (dev)
+ * out: Ytilde [B,K,d], row j-1 = y~_{n+j} (zeros for j > Kt);
+ *      krow [B,K] int32: the chain step at which the target must be evaluated on row j-1 of
+ *      Ytilde, i.e. n+j for j <= Kt-1, and -1 otherwise.  The target is evaluated on states
+ *      n .. n+Kt-1 only: state n is the window start (its prediction is D0) and the last draft is
+ *      not evaluated.                                                                    (dev) */
+int sd_draft(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int64_t* chain_id,
+             const float* D0, float* Ytilde, int32_t* krow, void* stream);
+
+/* Accept test + first rejection + reflection (Alg. "REJECTION ... same covariance"; detailed
+ * algorithm, second for-loop).  For j = 1 .. Kt, k = n+j-1, prev = y (j = 1) or Ytilde[j-2]:
+ *   m^q = a[k] prev + c[k] Dq[j-1];  m^p = a[k] prev + c[k] D0 (FROZEN) or mp[j-1] (EXPLICIT)
+ *   accept y~_{n+j} = Ytilde[j-1] as stated in the header comment; at the first rejection
+ *   y_out = m^q + sigma[k] (I - 2 e e^T) Z,  e = Delta/|Delta|, adv = j, rejected = 1;
+ *   with no rejection y_out = Ytilde[Kt-1], adv = Kt, rejected = 0.
+ * FROZEN: row 0 of Dq is never read (the window-start prediction IS D0, so Delta_1 = 0 exactly).
+ * in : y, n, chain_id as above; D0_or_mp = D0 [B,d] (FROZEN) or mp [B,K,d] (EXPLICIT);
+ *      Dq [B,K,d], row j-1 = D(y~_{n+j-1}, n+j-1); Ytilde [B,K,d]                     (dev)
+ * out: y_out [B,d]; adv [B] int32 in 1..Kt; rejected [B] uint8;
+ *      logratio, logu [B,K] float or NULL: the log acceptance ratio (already divided by tau) and
+ *      log u of every position j <= Kt (0 beyond), for diagnostics and parity checks.   (dev) */
+int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int64_t* chain_id,
+              const float* D0_or_mp, const float* Dq, const float* Ytilde, float* y_out,
+              int32_t* adv, uint8_t* rejected, float* logratio, float* logu, void* stream);
+
+/* n += adv; a chain with n = T is finished: its state goes to out[chain_id] and it leaves the
+ * batch; the others are packed to the front in their old order ("Set n <- k", while n < K).
+ * in : y_out [B,d], adv [B], rejected [B] or NULL (only used for the counters)          (dev)
+ * in place: y [B,d], n [B], chain_id [B] -- rewritten with the remaining chains        (dev)
+ * out: out [*, d], row index = chain_id (caller sizes it); B_active: dev int32, number of
+ *      remaining chains.  B_active may be the pointer given to sd_set_active_count.
+ *      counters: dev int64[4] or NULL, accumulated: {sum adv, chains processed, rejections,
+ *      windows}.  Needs the workspace. */
+int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv,
+               const uint8_t* rejected, float* y, int32_t* n, int64_t* chain_id, float* out,
+               int32_t* B_active, int64_t* counters, void* stream);
+
+/* One speculative window of unadjusted Langevin, fused (Alg. "Speculative Sampling for
+ * Unadjusted Langevin Diffusion", frozen-gradient proxy):  E(x) = -log sum_m w_m N(x; mu_m, s^2 I),
+ *   target  x - gamma grad E(x) + sqrt(2 gamma) w,   draft  x - gamma grad E(x_n) + sqrt(2 gamma) w,
+ *   Delta_j = sqrt(gamma/2) (grad E(y~_{j-1}) - grad E(x_n)).
+ * The context supplies T, K, d and the seed; its schedule arrays are not read.
+ * in : x [B,d], n [B], chain_id [B]; means [M,d]; logw [M] (log weights); comp_std = s; gamma (dev)
+ * out: x_out [B,d], adv [B], rejected [B] or NULL; logratio, logu [B,K] or NULL as in sd_verify. */
+int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
+                       const int64_t* chain_id, const float* means, const float* logw,
+                       float comp_std, int32_t M, float gamma, float* x_out, int32_t* adv,
+                       uint8_t* rejected, float* logratio, float* logu, void* stream);
+
+/* Text of the last error on this context (or of the last failed sd_create when ctx is NULL). */
+const char* sd_last_error(const sd_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SD_H */

@@ -1,0 +1,63 @@
+/* sdden.h -- C ABI of the target predictions D(y, k) used by the synthetic workloads.
+ *
+ * The method treats the target's drift as a black-box network ("b_t is approximated using a
+ * neural network", Sec. 3.1) that is evaluated on all drafted states of a window in one batched
+ * call (Alg. "Speculative Sampling for DDM", the (Par.) line).  These are the stand-ins with a
+ * plain definition; each maps rows X [R,d] with a per-row chain step krow [R] to out [R,d]:
+ *
+ *   gmm      E[x0 | x_t] of a diagonal-covariance Gaussian mixture (Bayes' rule over components)
+ *   lowrank  E[x0 | x_t] of N(mu, U U^T + s2 I): two skinny fp32 MFMA GEMMs in the eigenbasis of
+ *            U U^T with a per-row diagonal gain in between
+ *   mlp      3-layer SiLU MLP on [x ; sinusoidal(k)], bf16 weights, fp32 accumulation (bf16 MFMA)
+ *
+ * Conventions as in sd.h: "dev" pointers are caller-owned device memory, "host" pointers are read
+ * during the create call only.  Rows with krow < 0 are skipped: nothing is computed for them and
+ * their output row is left untouched.  `alpha_bar_state` (host, length T+1) is the signal level of
+ * chain state k: x = sqrt(ab) x0 + sqrt(1-ab) eps.  sdden_eval only enqueues kernels on `stream`.
+ */
+#ifndef SDDEN_H
+#define SDDEN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sdden sdden;     /* opaque; owns device copies of its parameters and tables */
+
+/* means, stds [M,d], logw [M] (log mixture weights), alpha_bar_state [T+1]: host. */
+int sdden_gmm_create(int32_t M, int32_t d, const float* means, const float* stds,
+                     const float* logw, int32_t T, const float* alpha_bar_state, sdden** out);
+
+/* mu [d], U [d,r] row-major, alpha_bar_state [T+1]: host.  Builds the eigenbasis Q [d,r] of U U^T
+ * and the per-step gain tables on the host in fp64. */
+int sdden_lowrank_create(int32_t d, int32_t r, const float* mu, const float* U, float s2,
+                         int32_t T, const float* alpha_bar_state, sdden** out);
+
+/* W1 [(d+E),H], W2 [H,H], W3 [H,d]: bf16 bit patterns, row = input feature; b1,b2 [H], b3 [d]:
+ * host.  Time embedding of width E: emb[i] = sin(k w_i), emb[E/2+i] = cos(k w_i),
+ * w_i = 10000^(-2i/E); its product with the last E rows of W1 is folded into a per-step bias
+ * table at create time.  Rmax = largest R sdden_eval will see (sizes the hidden activations). */
+int sdden_mlp_create(int32_t d, int32_t H, int32_t E, const uint16_t* W1, const float* b1,
+                     const uint16_t* W2, const float* b2, const uint16_t* W3, const float* b3,
+                     int32_t T, int32_t Rmax, sdden** out);
+
+/* out[r] = D(X[r], krow[r]) for every r < R with krow[r] >= 0.
+ * X [R,d], krow [R], out [R,d]: dev; X and out must not overlap.
+ * Optional `count`: dev int32 or NULL; when given only rows r < min(R, *count * rows_per_chain)
+ * are evaluated (matches sd_set_active_count; rows_per_chain = R / B of the call that sized R). */
+int sdden_eval(sdden* den, int32_t R, const float* X, const int32_t* krow, float* out,
+               void* stream);
+
+/* Restrict evaluation to the first (*count) * rows_per_chain rows; NULL removes the limit. */
+int sdden_set_active_count(sdden* den, const int32_t* count /*dev*/, int32_t rows_per_chain);
+
+int sdden_destroy(sdden* den);
+const char* sdden_last_error(const sdden* den);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDDEN_H */

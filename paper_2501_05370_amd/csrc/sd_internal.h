@@ -1,0 +1,48 @@
+// Shared host-side plumbing of the library: error text, HIP call checking, context layout.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+
+#include "../../include/sd.h"
+
+struct sd_ctx {
+  int32_t T = 0, d = 0, K = 0;
+  uint64_t seed = 0;
+  int mode = SD_DRAFT_FROZEN;
+  double tau = 1.0;
+  float* dev_a = nullptr;       // [T] each, one allocation of 3T floats
+  float* dev_c = nullptr;
+  float* dev_sigma = nullptr;
+  const int32_t* active = nullptr;
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+  int device = 0;
+  std::string err;
+};
+
+namespace sdi {
+
+inline int fail(std::string& slot, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  slot = buf;
+  return code;
+}
+
+#define SD_HIP_TRY(slot, expr)                                                          \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess)                                                               \
+      return sdi::fail(slot, SD_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace sdi

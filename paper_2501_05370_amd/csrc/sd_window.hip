@@ -1,0 +1,678 @@
+// Window kernels of speculative sampling for diffusion chains (gfx950) and their C entry points:
+// initial state, frozen draft rollout, accept / first-reject / reflect, advance + compaction.
+//
+// Paper: Alg. "Speculative Sampling for DDM", Alg. "REJECTION ... two Gaussians with same
+// covariance" (reflection maximal coupling), and the detailed algorithm of the appendix.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <new>
+
+#include "sd_internal.h"
+#include "sd_rng.h"
+
+namespace {
+
+constexpr int kBlock = 256;   // threads per workgroup (4 wavefronts of 64)
+constexpr int kJC = 16;       // window positions reduced together in the verify kernel
+
+std::string g_create_error;
+
+// ---------------------------------------------------------------------------------------------
+// small device helpers
+// ---------------------------------------------------------------------------------------------
+template <int VEC>
+struct Pack;
+template <>
+struct Pack<4> {
+  float v[4];
+  __device__ __forceinline__ void load(const float* p) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  __device__ __forceinline__ void store(float* p) const {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <>
+struct Pack<1> {
+  float v[1];
+  __device__ __forceinline__ void load(const float* p) { v[0] = *p; }
+  __device__ __forceinline__ void store(float* p) const { *p = v[0]; }
+};
+
+__device__ __forceinline__ int active_chains(const int32_t* active, int B) {
+  if (active == nullptr) return B;
+  const int a = *active;
+  return a < B ? (a < 0 ? 0 : a) : B;
+}
+
+// Sum over the `WIDTH` consecutive lanes this lane belongs to; every lane gets the total.
+template <int WIDTH>
+__device__ __forceinline__ double group_sum(double v) {
+#pragma unroll
+  for (int m = WIDTH / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, WIDTH);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Y_0 ~ N(0, Id)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void init_state_kernel(const int64_t* __restrict__ chain_id,
+                                                            float* __restrict__ y,
+                                                            int32_t* __restrict__ n, int B, int d,
+                                                            int nblk, uint64_t seed) {
+  const int64_t g = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (g >= static_cast<int64_t>(B) * nblk) return;
+  const int b = static_cast<int>(g / nblk);
+  const int blk = static_cast<int>(g % nblk);
+  float z[4];
+  sdrng::normal4(seed, chain_id[b], 0u, sdrng::kStreamInit, static_cast<uint32_t>(blk), z);
+  float* row = y + static_cast<int64_t>(b) * d;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (4 * blk + e < d) row[4 * blk + e] = z[e];
+  if (blk == 0) n[b] = 0;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Frozen draft rollout: one thread owns one Philox block (4 elements) of one chain and walks
+// the window, so the recurrence stays in registers and every drafted element is written once.
+// ---------------------------------------------------------------------------------------------
+struct DraftArgs {
+  const float *y, *D0;
+  const int32_t* n;
+  const int64_t* id;
+  float* Ytil;
+  int32_t* krow;
+  const float *a, *c, *sigma;
+  const int32_t* active;
+  int B, d, K, T, nblk;
+  uint64_t seed;
+};
+
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
+  const int64_t g = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  const int Bact = active_chains(p.active, p.B);
+  if (g >= static_cast<int64_t>(Bact) * p.nblk) return;
+  const int b = static_cast<int>(g / p.nblk);
+  const int blk = static_cast<int>(g % p.nblk);
+  const int i0 = 4 * blk;
+  const int n = p.n[b];
+  const int Kt = min(p.K, p.T - n);
+  const int64_t id = p.id[b];
+
+  float prev[4], d0[4];
+  const int64_t row0 = static_cast<int64_t>(b) * p.d + i0;
+  if (VEC == 4) {
+    Pack<4> t;
+    t.load(p.y + row0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) prev[e] = t.v[e];
+    t.load(p.D0 + row0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) d0[e] = t.v[e];
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool in = i0 + e < p.d;
+      prev[e] = in ? p.y[row0 + e] : 0.f;
+      d0[e] = in ? p.D0[row0 + e] : 0.f;
+    }
+  }
+  for (int j = 0; j < p.K; ++j) {       // position j+1 of the window, produces state n+j+1
+    float out[4] = {0.f, 0.f, 0.f, 0.f};
+    if (j < Kt) {
+      const int k = n + j;
+      const float a = p.a[k], c = p.c[k], s = p.sigma[k];
+      float z[4];
+      sdrng::normal4(p.seed, id, static_cast<uint32_t>(k + 1), sdrng::kStreamNoise,
+                     static_cast<uint32_t>(blk), z);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        prev[e] = fmaf(a, prev[e], fmaf(c, d0[e], s * z[e]));
+        out[e] = prev[e];
+      }
+    }
+    float* dst = p.Ytil + (static_cast<int64_t>(b) * p.K + j) * p.d + i0;
+    if (VEC == 4) {
+      *reinterpret_cast<float4*>(dst) = make_float4(out[0], out[1], out[2], out[3]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (i0 + e < p.d) dst[e] = out[e];
+    }
+    if (blk == 0) p.krow[static_cast<int64_t>(b) * p.K + j] = (j + 1 <= Kt - 1) ? n + j + 1 : -1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Accept test, first rejection, reflection.
+//
+// TPC threads cooperate on one chain (kBlock/TPC chains per workgroup).  Pass 1 streams the
+// chain's K rows of drafts and target predictions once: a thread owns a set of columns and
+// walks the window positions, keeping the previous row in registers, and accumulates the two
+// dot products of every position in fp64.  The per-position sums are reduced with wavefront
+// shuffles (and LDS across wavefronts), the first kJC lanes of the chain run the accept test of
+// one position each, and a ballot finds the first rejection.  Pass 2 re-reads only the
+// rejected row and writes the reflected state (or copies the last draft).
+//
+// All loop bounds depend on K only, so every barrier and shuffle is reached by all threads.
+// ---------------------------------------------------------------------------------------------
+struct VerifyArgs {
+  const float *y, *D0mp, *Dq, *Ytil;
+  const int32_t* n;
+  const int64_t* id;
+  float* y_out;
+  int32_t* adv;
+  uint8_t* rej;
+  float *logratio, *logu;
+  const float *a, *c, *sigma;
+  const int32_t* active;
+  int B, d, K, T;
+  uint64_t seed;
+  double inv_tau;
+};
+
+template <int TPC, int VEC, bool FROZEN>
+__global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
+  constexpr int CPW = kBlock / TPC;                 // chains per workgroup
+  constexpr int WAVES = TPC / 64;                   // wavefronts per chain (0: sub-wavefront)
+  constexpr int WIDTH = TPC < 64 ? TPC : 64;
+  static_assert(TPC >= kJC, "one lane per window position of a chunk");
+
+  __shared__ double sh_part[WAVES > 1 ? WAVES : 1][2 * kJC];
+  __shared__ int sh_jr[CPW];
+  __shared__ double sh_coef[CPW];
+
+  const int slot = threadIdx.x / TPC;
+  const int t = threadIdx.x % TPC;
+  const int b_raw = blockIdx.x * CPW + slot;
+  const int Bact = active_chains(p.active, p.B);
+  const bool valid = b_raw < Bact;
+  const int b = valid ? b_raw : 0;
+  const int n = valid ? p.n[b] : 0;
+  const int Kt = valid ? max(0, min(p.K, p.T - n)) : 0;
+  const int64_t id = valid ? p.id[b] : 0;
+  const int ncol = p.d / VEC;
+  const int64_t rowB = static_cast<int64_t>(b) * p.d;            // offset of y[b], D0[b]
+  const int64_t winB = static_cast<int64_t>(b) * p.K * p.d;      // offset of Ytil[b,0], Dq[b,0]
+
+  if (t == 0) sh_jr[slot] = -1;
+  __syncthreads();
+
+  for (int jc = 0; jc < p.K; jc += kJC) {
+    float ak[kJC], ck[kJC];
+#pragma unroll
+    for (int jj = 0; jj < kJC; ++jj) {
+      const bool in = jc + jj < Kt;
+      ak[jj] = in ? p.a[n + jc + jj] : 0.f;
+      ck[jj] = in ? p.c[n + jc + jj] : 0.f;
+    }
+    double s1[kJC], s2[kJC];
+#pragma unroll
+    for (int jj = 0; jj < kJC; ++jj) s1[jj] = s2[jj] = 0.0;
+
+    if (jc < Kt) {
+      for (int col = t; col < ncol; col += TPC) {
+        const int64_t off = static_cast<int64_t>(col) * VEC;
+        Pack<VEC> prev, d0;
+        if (jc == 0) prev.load(p.y + rowB + off);
+        else prev.load(p.Ytil + winB + static_cast<int64_t>(jc - 1) * p.d + off);
+        if (FROZEN) d0.load(p.D0mp + rowB + off);
+#pragma unroll
+        for (int jj = 0; jj < kJC; ++jj) {
+          const int j = jc + jj;
+          if (j < Kt) {
+            const int64_t r = winB + static_cast<int64_t>(j) * p.d + off;
+            Pack<VEC> cur, dq, mp;
+            cur.load(p.Ytil + r);
+            if (FROZEN) {
+              if (j > 0) dq.load(p.Dq + r);
+            } else {
+              dq.load(p.Dq + r);
+              mp.load(p.D0mp + r);
+            }
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+              double w, dl;      // w = sigma*Z, dl = (sigma/c)*Delta (FROZEN) or sigma*Delta
+              if (FROZEN) {
+                w = static_cast<double>(cur.v[e]) - static_cast<double>(ak[jj]) * prev.v[e] -
+                    static_cast<double>(ck[jj]) * d0.v[e];
+                dl = (j > 0) ? static_cast<double>(d0.v[e]) - static_cast<double>(dq.v[e]) : 0.0;
+              } else {
+                w = static_cast<double>(cur.v[e]) - static_cast<double>(mp.v[e]);
+                dl = static_cast<double>(mp.v[e]) - (static_cast<double>(ak[jj]) * prev.v[e] +
+                                                     static_cast<double>(ck[jj]) * dq.v[e]);
+              }
+              s1[jj] = fma(w, dl, s1[jj]);
+              s2[jj] = fma(dl, dl, s2[jj]);
+            }
+            prev = cur;
+          }
+        }
+      }
+    }
+
+    // ---- reduce the 2*kJC sums over the chain's threads
+    double mine1 = 0.0, mine2 = 0.0;      // lane t < kJC ends up with the sums of position jc+t
+#pragma unroll
+    for (int jj = 0; jj < kJC; ++jj) {
+      s1[jj] = group_sum<WIDTH>(s1[jj]);
+      s2[jj] = group_sum<WIDTH>(s2[jj]);
+    }
+    if (WAVES > 1) {
+      const int wave = t / 64;
+      if ((t & 63) == 0) {
+#pragma unroll
+        for (int jj = 0; jj < kJC; ++jj) {
+          sh_part[wave][jj] = s1[jj];
+          sh_part[wave][kJC + jj] = s2[jj];
+        }
+      }
+      __syncthreads();
+      if (t < kJC) {
+#pragma unroll
+        for (int w = 0; w < (WAVES > 1 ? WAVES : 1); ++w) {
+          mine1 += sh_part[w][t];
+          mine2 += sh_part[w][kJC + t];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int jj = 0; jj < kJC; ++jj)
+        if (t == jj) { mine1 = s1[jj]; mine2 = s2[jj]; }
+    }
+
+    // ---- accept test of position j = jc + t by the chain's first kJC lanes
+    bool reject = false;
+    double coef = 0.0;
+    if (t < kJC) {
+      const int j = jc + t;
+      const bool inwin = j < Kt;
+      double lr = 0.0, lu = 0.0;
+      if (inwin) {
+        const int k = n + j;
+        const double sg = p.sigma[k];
+        const double inv_s2 = 1.0 / (sg * sg);
+        double S1, S2;                       // Z.Delta and |Delta|^2
+        if (FROZEN) {
+          const double c = p.c[k];
+          S1 = mine1 * c * inv_s2;
+          S2 = mine2 * c * c * inv_s2;
+        } else {
+          S1 = mine1 * inv_s2;
+          S2 = mine2 * inv_s2;
+        }
+        lr = (-S1 - 0.5 * S2) * p.inv_tau;
+        lu = sdrng::log_uniform(p.seed, id, static_cast<uint32_t>(k + 1));
+        reject = !(S2 == 0.0 || lu <= fmin(0.0, lr));
+        coef = S2 > 0.0 ? S1 / S2 : 0.0;
+      }
+      if (valid && j < p.K) {
+        if (p.logratio) p.logratio[static_cast<int64_t>(b) * p.K + j] = static_cast<float>(lr);
+        if (p.logu) p.logu[static_cast<int64_t>(b) * p.K + j] = static_cast<float>(lu);
+      }
+    }
+    const unsigned long long ballot = __ballot(reject);
+    const int lane = threadIdx.x & 63;
+    const unsigned long long mine =
+        (TPC < 64) ? ((ballot >> (lane & ~(TPC - 1))) & ((1ull << kJC) - 1ull)) : (ballot & ((1ull << kJC) - 1ull));
+    if (t < kJC && reject && sh_jr[slot] < 0 && (mine & ((1ull << t) - 1ull)) == 0ull) {
+      // lowest rejecting position of this chunk, and no earlier chunk rejected
+      sh_jr[slot] = jc + t;
+      sh_coef[slot] = coef;
+    }
+    __syncthreads();
+  }
+
+  // ---- pass 2: write the state the chain keeps
+  const int jr = sh_jr[slot];
+  if (!valid) return;
+  if (t == 0) {
+    p.adv[b] = jr >= 0 ? jr + 1 : Kt;
+    if (p.rej) p.rej[b] = jr >= 0 ? 1 : 0;
+  }
+  float* dst = p.y_out + rowB;
+  if (jr < 0) {
+    const float* src = Kt > 0 ? p.Ytil + winB + static_cast<int64_t>(Kt - 1) * p.d : p.y + rowB;
+    for (int col = t; col < ncol; col += TPC) {
+      Pack<VEC> v;
+      v.load(src + static_cast<int64_t>(col) * VEC);
+      v.store(dst + static_cast<int64_t>(col) * VEC);
+    }
+    return;
+  }
+  const int k = n + jr;
+  const double a = p.a[k], c = p.c[k];
+  const double two_coef = 2.0 * sh_coef[slot];
+  const float* prevrow = jr == 0 ? p.y + rowB : p.Ytil + winB + static_cast<int64_t>(jr - 1) * p.d;
+  const int64_t r = winB + static_cast<int64_t>(jr) * p.d;
+  for (int col = t; col < ncol; col += TPC) {
+    const int64_t off = static_cast<int64_t>(col) * VEC;
+    Pack<VEC> prev, cur, dq, x, o;
+    prev.load(prevrow + off);
+    cur.load(p.Ytil + r + off);
+    dq.load(p.Dq + r + off);
+    if (FROZEN) x.load(p.D0mp + rowB + off);
+    else x.load(p.D0mp + r + off);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const double mq = a * prev.v[e] + c * dq.v[e];
+      const double mp = FROZEN ? a * prev.v[e] + c * x.v[e] : static_cast<double>(x.v[e]);
+      // Y = m^q + sigma (Z - 2 (Z.Delta/|Delta|^2) Delta),  sigma Z = cur - m^p, sigma Delta = m^p - m^q
+      o.v[e] = static_cast<float>(mq + (static_cast<double>(cur.v[e]) - mp) - two_coef * (mp - mq));
+    }
+    o.store(dst + off);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Advance + compaction.  One workgroup scans the batch in chunks of its size: dest <= source
+// always holds for a stable compaction to the front, and a chunk reads all its inputs before it
+// writes, so n and chain_id can be rewritten in place.  A second kernel moves the states.
+// ---------------------------------------------------------------------------------------------
+constexpr int kScanBlock = 1024;
+
+__global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
+    const int32_t* __restrict__ adv, const uint8_t* __restrict__ rej, int32_t* n, int64_t* chain_id,
+    int32_t* __restrict__ dest, int64_t* __restrict__ outrow, int32_t* B_active, int64_t* counters,
+    const int32_t* active, int B, int T) {
+  __shared__ int wave_tot[kScanBlock / 64];
+  __shared__ int sh_base;
+  __shared__ long long sh_cnt[3];
+  const int Bact = active_chains(active, B);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) { sh_base = 0; sh_cnt[0] = sh_cnt[1] = sh_cnt[2] = 0; }
+  __syncthreads();
+  long long my_adv = 0, my_rej = 0;
+  for (int start = 0; start < Bact; start += kScanBlock) {
+    const int b = start + tid;
+    const bool in = b < Bact;
+    int nn = 0;
+    int64_t id = 0;
+    bool keep = false;
+    if (in) {
+      nn = n[b] + adv[b];
+      id = chain_id[b];
+      keep = nn < T;
+      my_adv += adv[b];
+      if (rej) my_rej += rej[b];
+    }
+    const unsigned long long m = __ballot(keep);
+    const int before = __popcll(m & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_tot[wave] = __popcll(m);
+    __syncthreads();
+    int offset = sh_base;
+    for (int w = 0; w < wave; ++w) offset += wave_tot[w];
+    if (in) {
+      if (keep) {
+        const int dpos = offset + before;
+        dest[b] = dpos;
+        n[dpos] = nn;
+        chain_id[dpos] = id;
+      } else {
+        dest[b] = -1;
+        outrow[b] = id;
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int tot = 0;
+      for (int w = 0; w < kScanBlock / 64; ++w) tot += wave_tot[w];
+      sh_base += tot;
+    }
+    __syncthreads();
+  }
+  if (counters) {
+    atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[0]), static_cast<unsigned long long>(my_adv));
+    atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[2]), static_cast<unsigned long long>(my_rej));
+  }
+  __syncthreads();
+  if (tid == 0) {
+    *B_active = sh_base;
+    if (counters) {
+      counters[0] += sh_cnt[0];
+      counters[1] += Bact;
+      counters[2] += sh_cnt[2];
+      counters[3] += Bact > 0 ? 1 : 0;
+    }
+  }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __restrict__ y_out,
+                                                              const int32_t* __restrict__ dest,
+                                                              const int64_t* __restrict__ outrow,
+                                                              float* __restrict__ y,
+                                                              float* __restrict__ out, int Bprev,
+                                                              int d, int chunks) {
+  // Bprev = number of chains that entered the window (host bound; rows beyond the device-side
+  // count carry dest = -2 from the fill below and are skipped).
+  const int b = blockIdx.x / chunks;
+  const int chunk = blockIdx.x % chunks;
+  if (b >= Bprev) return;
+  const int dpos = dest[b];
+  if (dpos == -2) return;
+  float* dst = dpos >= 0 ? y + static_cast<int64_t>(dpos) * d : out + outrow[b] * d;
+  const float* src = y_out + static_cast<int64_t>(b) * d;
+  const int ncol = d / VEC;
+  const int col = chunk * kBlock + threadIdx.x;
+  if (col < ncol) {
+    Pack<VEC> v;
+    v.load(src + static_cast<int64_t>(col) * VEC);
+    v.store(dst + static_cast<int64_t>(col) * VEC);
+  }
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+int check_ctx(sd_ctx* ctx) { return ctx ? SD_OK : SD_ERR_ARG; }
+
+template <int TPC, int VEC>
+void launch_verify(bool frozen, int B, hipStream_t st, const VerifyArgs& p) {
+  constexpr int CPW = kBlock / TPC;
+  const unsigned grid = static_cast<unsigned>((B + CPW - 1) / CPW);
+  if (frozen) hipLaunchKernelGGL((verify_kernel<TPC, VEC, true>), dim3(grid), dim3(kBlock), 0, st, p);
+  else        hipLaunchKernelGGL((verify_kernel<TPC, VEC, false>), dim3(grid), dim3(kBlock), 0, st, p);
+}
+
+}  // namespace
+
+// =============================================================================================
+// C entry points
+// =============================================================================================
+extern "C" {
+
+int sd_create(const sd_schedule* s, int32_t d, int32_t K, sd_ctx** out) {
+  if (!s || !out || !s->a || !s->c || !s->sigma)
+    return sdi::fail(g_create_error, SD_ERR_ARG, "sd_create: null argument");
+  if (s->T <= 0 || d <= 0 || K <= 0 || K > SD_MAX_WINDOW)
+    return sdi::fail(g_create_error, SD_ERR_ARG, "sd_create: need T>0, d>0, 1<=K<=%d (T=%d d=%d K=%d)",
+                     SD_MAX_WINDOW, s->T, d, K);
+  for (int k = 0; k < s->T; ++k) {
+    if (!std::isfinite(s->a[k]) || !std::isfinite(s->c[k]) || !std::isfinite(s->sigma[k]))
+      return sdi::fail(g_create_error, SD_ERR_SCHEDULE, "sd_create: non-finite coefficient at step %d", k);
+    if (!(s->sigma[k] > 0.f))
+      return sdi::fail(g_create_error, SD_ERR_SCHEDULE, "sd_create: sigma[%d]=%g must be > 0", k,
+                       static_cast<double>(s->sigma[k]));
+  }
+  sd_ctx* ctx = new (std::nothrow) sd_ctx;
+  if (!ctx) return sdi::fail(g_create_error, SD_ERR_ARG, "sd_create: out of host memory");
+  ctx->T = s->T; ctx->d = d; ctx->K = K;
+  hipError_t e = hipGetDevice(&ctx->device);
+  float* dev = nullptr;
+  if (e == hipSuccess) e = hipMalloc(&dev, sizeof(float) * 3 * static_cast<size_t>(s->T));
+  if (e == hipSuccess) e = hipMemcpy(dev, s->a, sizeof(float) * s->T, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(dev + s->T, s->c, sizeof(float) * s->T, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(dev + 2 * s->T, s->sigma, sizeof(float) * s->T, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    if (dev) (void)hipFree(dev);
+    delete ctx;
+    return sdi::fail(g_create_error, SD_ERR_HIP, "sd_create: %s", hipGetErrorString(e));
+  }
+  ctx->dev_a = dev; ctx->dev_c = dev + s->T; ctx->dev_sigma = dev + 2 * s->T;
+  *out = ctx;
+  return SD_OK;
+}
+
+int sd_destroy(sd_ctx* ctx) {
+  if (!ctx) return SD_ERR_ARG;
+  if (ctx->dev_a) (void)hipFree(ctx->dev_a);
+  delete ctx;
+  return SD_OK;
+}
+
+int sd_set_seed(sd_ctx* ctx, uint64_t seed) {
+  if (!ctx) return SD_ERR_ARG;
+  ctx->seed = seed;
+  return SD_OK;
+}
+
+int sd_set_draft_mode(sd_ctx* ctx, int mode) {
+  if (!ctx) return SD_ERR_ARG;
+  if (mode != SD_DRAFT_FROZEN && mode != SD_DRAFT_EXPLICIT)
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_set_draft_mode: unknown mode %d", mode);
+  ctx->mode = mode;
+  return SD_OK;
+}
+
+int sd_set_temperature(sd_ctx* ctx, float tau) {
+  if (!ctx) return SD_ERR_ARG;
+  if (!(tau > 0.f) || !std::isfinite(tau))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_set_temperature: tau=%g must be finite and > 0",
+                     static_cast<double>(tau));
+  ctx->tau = tau;
+  return SD_OK;
+}
+
+int sd_set_active_count(sd_ctx* ctx, const int32_t* count) {
+  if (!ctx) return SD_ERR_ARG;
+  ctx->active = count;
+  return SD_OK;
+}
+
+size_t sd_workspace_bytes(const sd_ctx* ctx, int32_t Bmax) {
+  if (!ctx || Bmax <= 0) return 0;
+  // dest int32[B] (padded to 8 bytes) + outrow int64[B]
+  const size_t b = static_cast<size_t>(Bmax);
+  return ((b * 4 + 7) / 8) * 8 + b * 8;
+}
+
+int sd_set_workspace(sd_ctx* ctx, void* workspace, size_t bytes) {
+  if (!ctx) return SD_ERR_ARG;
+  if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 7u))
+    return sdi::fail(ctx->err, SD_ERR_WORKSPACE, "sd_set_workspace: buffer must be 8-byte aligned");
+  ctx->ws = workspace;
+  ctx->ws_bytes = workspace ? bytes : 0;
+  return SD_OK;
+}
+
+int sd_init_state(sd_ctx* ctx, int32_t B, const int64_t* chain_id, float* y, int32_t* n, void* stream) {
+  if (int rc = check_ctx(ctx)) return rc;
+  if (B < 0 || (B > 0 && (!chain_id || !y || !n)))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_init_state: bad argument");
+  if (B == 0) return SD_OK;
+  const int nblk = (ctx->d + 3) / 4;
+  const int64_t total = static_cast<int64_t>(B) * nblk;
+  const int64_t grid = (total + kBlock - 1) / kBlock;
+  if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_init_state: B*d too large");
+  hipLaunchKernelGGL(init_state_kernel, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0,
+                     static_cast<hipStream_t>(stream), chain_id, y, n, B, ctx->d, nblk, ctx->seed);
+  SD_HIP_TRY(ctx->err, hipGetLastError());
+  return SD_OK;
+}
+
+int sd_draft(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int64_t* chain_id,
+             const float* D0, float* Ytilde, int32_t* krow, void* stream) {
+  if (int rc = check_ctx(ctx)) return rc;
+  if (ctx->mode != SD_DRAFT_FROZEN)
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_draft: only the frozen drafter is rolled out by the library; "
+                                           "in EXPLICIT mode the caller produces the drafts and their means");
+  if (B < 0 || (B > 0 && (!y || !n || !chain_id || !D0 || !Ytilde || !krow)))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_draft: bad argument");
+  if (B == 0) return SD_OK;
+  DraftArgs p;
+  p.y = y; p.D0 = D0; p.n = n; p.id = chain_id; p.Ytil = Ytilde; p.krow = krow;
+  p.a = ctx->dev_a; p.c = ctx->dev_c; p.sigma = ctx->dev_sigma; p.active = ctx->active;
+  p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.nblk = (ctx->d + 3) / 4; p.seed = ctx->seed;
+  const int64_t total = static_cast<int64_t>(B) * p.nblk;
+  const int64_t grid = (total + kBlock - 1) / kBlock;
+  if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_draft: B*d too large");
+  const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y) && sdi::aligned16(D0) && sdi::aligned16(Ytilde);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (vec) hipLaunchKernelGGL(draft_frozen_kernel<4>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st, p);
+  else     hipLaunchKernelGGL(draft_frozen_kernel<1>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st, p);
+  SD_HIP_TRY(ctx->err, hipGetLastError());
+  return SD_OK;
+}
+
+int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int64_t* chain_id,
+              const float* D0_or_mp, const float* Dq, const float* Ytilde, float* y_out,
+              int32_t* adv, uint8_t* rejected, float* logratio, float* logu, void* stream) {
+  if (int rc = check_ctx(ctx)) return rc;
+  if (B < 0 || (B > 0 && (!y || !n || !chain_id || !D0_or_mp || !Dq || !Ytilde || !y_out || !adv)))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_verify: bad argument");
+  if (B == 0) return SD_OK;
+  VerifyArgs p;
+  p.y = y; p.D0mp = D0_or_mp; p.Dq = Dq; p.Ytil = Ytilde; p.n = n; p.id = chain_id;
+  p.y_out = y_out; p.adv = adv; p.rej = rejected; p.logratio = logratio; p.logu = logu;
+  p.a = ctx->dev_a; p.c = ctx->dev_c; p.sigma = ctx->dev_sigma; p.active = ctx->active;
+  p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.seed = ctx->seed; p.inv_tau = 1.0 / ctx->tau;
+  const bool frozen = ctx->mode == SD_DRAFT_FROZEN;
+  const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y) && sdi::aligned16(D0_or_mp) &&
+                   sdi::aligned16(Dq) && sdi::aligned16(Ytilde) && sdi::aligned16(y_out);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int ncol = vec ? ctx->d / 4 : ctx->d;
+  if (vec) {
+    if (ncol <= 32)       launch_verify<16, 4>(frozen, B, st, p);
+    else if (ncol <= 256) launch_verify<64, 4>(frozen, B, st, p);
+    else                  launch_verify<256, 4>(frozen, B, st, p);
+  } else {
+    if (ncol <= 32)       launch_verify<16, 1>(frozen, B, st, p);
+    else if (ncol <= 256) launch_verify<64, 1>(frozen, B, st, p);
+    else                  launch_verify<256, 1>(frozen, B, st, p);
+  }
+  SD_HIP_TRY(ctx->err, hipGetLastError());
+  return SD_OK;
+}
+
+int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, const uint8_t* rejected,
+               float* y, int32_t* n, int64_t* chain_id, float* out, int32_t* B_active,
+               int64_t* counters, void* stream) {
+  if (int rc = check_ctx(ctx)) return rc;
+  if (B < 0 || !B_active || (B > 0 && (!y_out || !adv || !y || !n || !chain_id || !out)))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_advance: bad argument");
+  if (B > 0 && (!ctx->ws || ctx->ws_bytes < sd_workspace_bytes(ctx, B)))
+    return sdi::fail(ctx->err, SD_ERR_WORKSPACE, "sd_advance: workspace of %zu bytes needed for B=%d, have %zu",
+                     sd_workspace_bytes(ctx, B), B, ctx->ws_bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int32_t* dest = static_cast<int32_t*>(ctx->ws);
+  int64_t* outrow = reinterpret_cast<int64_t*>(static_cast<char*>(ctx->ws) + ((static_cast<size_t>(B) * 4 + 7) / 8) * 8);
+  if (B > 0 && ctx->active) {   // rows beyond the device-side count must be recognisable
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((B + 255) / 256), dim3(256), 0, st, dest, B, -2);
+  }
+  hipLaunchKernelGGL(advance_scan_kernel, dim3(1), dim3(kScanBlock), 0, st, adv, rejected, n, chain_id,
+                     dest, outrow, B_active, counters, ctx->active, B, ctx->T);
+  if (B > 0) {
+    const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y_out) && sdi::aligned16(y) && sdi::aligned16(out);
+    const int ncol = vec ? ctx->d / 4 : ctx->d;
+    const int chunks = (ncol + kBlock - 1) / kBlock;
+    const int64_t grid = static_cast<int64_t>(B) * chunks;
+    if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_advance: B*d too large");
+    if (vec) hipLaunchKernelGGL(advance_move_kernel<4>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
+                                y_out, dest, outrow, y, out, B, ctx->d, chunks);
+    else     hipLaunchKernelGGL(advance_move_kernel<1>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
+                                y_out, dest, outrow, y, out, B, ctx->d, chunks);
+  }
+  SD_HIP_TRY(ctx->err, hipGetLastError());
+  return SD_OK;
+}
+
+const char* sd_last_error(const sd_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,194 @@
+// Posterior mean of a diagonal-covariance Gaussian mixture under the forward noising
+// x_t = sqrt(ab) x0 + sqrt(1-ab) eps -- the analytic stand-in for the target network
+// (paper Sec. 3.1 treats the drift as a black box; the low-dimensional mixture study of the
+// experiments has this shape).  Also the generic entry points of sdden.h.
+//
+//   r_m(x)  = softmax_m( log w_m + log N(x; sqrt(ab) mu_m, diag(ab s_m^2 + 1-ab)) )
+//   D(x,k)  = sum_m r_m(x) ( mu_m + sqrt(ab) s_m^2 / v_m * (x - sqrt(ab) mu_m) )
+//
+// One wavefront per row.  Phase 1: a lane owns a component and walks the coordinates (no
+// cross-lane reduction for the logits).  Phase 2: a lane owns a coordinate and walks the
+// components.  All arithmetic in fp64: the rows are few and small, and the responsibilities are
+// exponentials of sums of d terms.
+#include <cmath>
+#include <new>
+#include <vector>
+
+#include "sdden_internal.h"
+
+namespace sdi {
+std::string g_den_create_error;
+}
+
+namespace {
+
+constexpr int kRowsPerBlock = 4;
+
+struct GmmArgs {
+  const float* X;
+  const int32_t* krow;
+  float* out;
+  const float *mu, *sd;      // [M,d]  component means and stds
+  const float *muT, *sdT;    // [d,M]  the same, transposed
+  const double* cst;         // [T,M]  log w_m - 1/2 sum_i log v_mi(k)
+  const float* ab;           // [T+1]
+  const int32_t* active;
+  int rows_per_chain;
+  int R, d, M;
+};
+
+__global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_kernel(GmmArgs p) {
+  extern __shared__ double smem[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  double* rs = smem + static_cast<size_t>(wave) * (p.M + p.d);   // [M] responsibilities
+  double* xs = rs + p.M;                                          // [d] the row
+  const int r = blockIdx.x * kRowsPerBlock + wave;
+  const int Ract = sdi::active_rows(p.active, p.rows_per_chain, p.R);
+  const int k = r < Ract ? p.krow[r] : -1;
+  if (k < 0) return;                        // whole wavefront leaves together; no barriers used
+  const double ab = p.ab[k];
+  const double sab = sqrt(ab), om = 1.0 - ab;
+  const float* x = p.X + static_cast<int64_t>(r) * p.d;
+  for (int i = lane; i < p.d; i += 64) xs[i] = x[i];
+  __builtin_amdgcn_wave_barrier();
+  __threadfence_block();
+
+  double mx = -INFINITY;
+  for (int m = lane; m < p.M; m += 64) {
+    double q = 0.0;
+    for (int i = 0; i < p.d; ++i) {
+      const double diff = xs[i] - sab * p.muT[static_cast<int64_t>(i) * p.M + m];
+      const double sd = p.sdT[static_cast<int64_t>(i) * p.M + m];
+      const double v = ab * sd * sd + om;
+      q += diff * diff / v;
+    }
+    const double logit = p.cst[static_cast<int64_t>(k) * p.M + m] - 0.5 * q;
+    rs[m] = logit;
+    mx = fmax(mx, logit);
+  }
+  for (int s = 32; s >= 1; s >>= 1) mx = fmax(mx, __shfl_xor(mx, s, 64));
+  double sum = 0.0;
+  for (int m = lane; m < p.M; m += 64) {
+    const double e = exp(rs[m] - mx);
+    rs[m] = e;
+    sum += e;
+  }
+  for (int s = 32; s >= 1; s >>= 1) sum += __shfl_xor(sum, s, 64);
+  const double inv = 1.0 / sum;
+  __builtin_amdgcn_wave_barrier();
+  __threadfence_block();
+
+  float* o = p.out + static_cast<int64_t>(r) * p.d;
+  for (int i = lane; i < p.d; i += 64) {
+    const double xi = xs[i];
+    double acc = 0.0;
+    for (int m = 0; m < p.M; ++m) {
+      const double mu = p.mu[static_cast<int64_t>(m) * p.d + i];
+      const double sd = p.sd[static_cast<int64_t>(m) * p.d + i];
+      const double s2 = sd * sd;
+      const double v = ab * s2 + om;
+      acc += rs[m] * (mu + sab * s2 / v * (xi - sab * mu));
+    }
+    o[i] = static_cast<float>(acc * inv);
+  }
+}
+
+struct GmmDenoiser final : sdden {
+  int M = 0;
+  float* dev_f = nullptr;     // mu, sd, muT, sdT, ab
+  double* dev_cst = nullptr;
+  ~GmmDenoiser() override {
+    if (dev_f) (void)hipFree(dev_f);
+    if (dev_cst) (void)hipFree(dev_cst);
+  }
+  int eval(int R, const float* X, const int32_t* krow, float* out, hipStream_t st) override {
+    GmmArgs p;
+    const size_t md = static_cast<size_t>(M) * d;
+    p.X = X; p.krow = krow; p.out = out;
+    p.mu = dev_f; p.sd = dev_f + md; p.muT = dev_f + 2 * md; p.sdT = dev_f + 3 * md; p.ab = dev_f + 4 * md;
+    p.cst = dev_cst; p.active = active; p.rows_per_chain = rows_per_chain;
+    p.R = R; p.d = d; p.M = M;
+    const size_t shmem = sizeof(double) * kRowsPerBlock * static_cast<size_t>(M + d);
+    const unsigned grid = static_cast<unsigned>((R + kRowsPerBlock - 1) / kRowsPerBlock);
+    hipLaunchKernelGGL(gmm_posterior_mean_kernel, dim3(grid), dim3(64 * kRowsPerBlock), shmem, st, p);
+    SD_HIP_TRY(err, hipGetLastError());
+    return SD_OK;
+  }
+};
+
+}  // namespace
+
+extern "C" {
+
+int sdden_gmm_create(int32_t M, int32_t d, const float* means, const float* stds, const float* logw,
+                     int32_t T, const float* alpha_bar_state, sdden** out) {
+  std::string& E = sdi::g_den_create_error;
+  if (!means || !stds || !logw || !alpha_bar_state || !out || M <= 0 || d <= 0 || T <= 0)
+    return sdi::fail(E, SD_ERR_ARG, "sdden_gmm_create: bad argument");
+  if (static_cast<size_t>(M + d) * sizeof(double) * kRowsPerBlock > 60000)
+    return sdi::fail(E, SD_ERR_UNSUPPORTED, "sdden_gmm_create: M+d=%d too large for the LDS staging", M + d);
+  const size_t md = static_cast<size_t>(M) * d;
+  std::vector<float> h(4 * md + T + 1);
+  std::vector<double> cst(static_cast<size_t>(T) * M);
+  for (int m = 0; m < M; ++m)
+    for (int i = 0; i < d; ++i) {
+      const float mu = means[m * static_cast<size_t>(d) + i], s = stds[m * static_cast<size_t>(d) + i];
+      if (!(s > 0.f)) return sdi::fail(E, SD_ERR_ARG, "sdden_gmm_create: stds must be > 0");
+      h[m * static_cast<size_t>(d) + i] = mu;
+      h[md + m * static_cast<size_t>(d) + i] = s;
+      h[2 * md + i * static_cast<size_t>(M) + m] = mu;
+      h[3 * md + i * static_cast<size_t>(M) + m] = s;
+    }
+  for (int k = 0; k <= T; ++k) h[4 * md + k] = alpha_bar_state[k];
+  for (int k = 0; k < T; ++k) {
+    const double ab = alpha_bar_state[k];
+    for (int m = 0; m < M; ++m) {
+      double ld = 0.0;
+      for (int i = 0; i < d; ++i) {
+        const double sd = h[md + m * static_cast<size_t>(d) + i];
+        ld += std::log(ab * sd * sd + (1.0 - ab));
+      }
+      cst[static_cast<size_t>(k) * M + m] = static_cast<double>(logw[m]) - 0.5 * ld;
+    }
+  }
+  GmmDenoiser* g = new (std::nothrow) GmmDenoiser;
+  if (!g) return sdi::fail(E, SD_ERR_ARG, "sdden_gmm_create: out of host memory");
+  g->d = d; g->T = T; g->M = M;
+  hipError_t e = hipMalloc(&g->dev_f, h.size() * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc(&g->dev_cst, cst.size() * sizeof(double));
+  if (e == hipSuccess) e = hipMemcpy(g->dev_f, h.data(), h.size() * sizeof(float), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(g->dev_cst, cst.data(), cst.size() * sizeof(double), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    delete g;
+    return sdi::fail(E, SD_ERR_HIP, "sdden_gmm_create: %s", hipGetErrorString(e));
+  }
+  *out = g;
+  return SD_OK;
+}
+
+int sdden_eval(sdden* den, int32_t R, const float* X, const int32_t* krow, float* out, void* stream) {
+  if (!den) return SD_ERR_ARG;
+  if (R < 0 || (R > 0 && (!X || !krow || !out))) return sdi::fail(den->err, SD_ERR_ARG, "sdden_eval: bad argument");
+  if (R == 0) return SD_OK;
+  return den->eval(R, X, krow, out, static_cast<hipStream_t>(stream));
+}
+
+int sdden_set_active_count(sdden* den, const int32_t* count, int32_t rows_per_chain) {
+  if (!den) return SD_ERR_ARG;
+  if (count && rows_per_chain <= 0) return sdi::fail(den->err, SD_ERR_ARG, "sdden_set_active_count: rows_per_chain must be > 0");
+  den->active = count;
+  den->rows_per_chain = count ? rows_per_chain : 1;
+  return SD_OK;
+}
+
+int sdden_destroy(sdden* den) {
+  if (!den) return SD_ERR_ARG;
+  delete den;
+  return SD_OK;
+}
+
+const char* sdden_last_error(const sdden* den) {
+  return den ? den->err.c_str() : sdi::g_den_create_error.c_str();
+}
+
+}  // extern "C"

@@ -1,0 +1,137 @@
+"""GPU parity of whole runs: the window loop fed window by window with the oracle's state, the
+free-running sampler against the oracle's trajectories, and the fused Langevin window.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import langevin as L
+from oracle import speculative as S
+from oracle.denoisers import GMMDenoiser, GMMScore
+
+from _gpu import as_f32_f64, decisions_match, dev, f32, host, make_context, rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+def test_c1_window_by_window_and_free_running():
+    """Config 1 (toy DDPM, d=2, 64 chains, 100 steps, K=4, seed 0), all windows.
+    (a) every window of the oracle's run is replayed on the GPU from the oracle's state;
+    (b) the GPU sampler runs by itself; chains whose decisions never hit a near tie must end
+        within tolerance of the oracle's final state."""
+    from paper_2501_05370_amd.binding import Denoiser
+    from paper_2501_05370_amd.sampler import DiffusionSampler
+    from oracle import philox
+    cfg = W.make_config("c1")
+    den = GMMDenoiser(cfg.params, cfg.schedule.alpha_bar_state)
+    B, K, d, T = cfg.B, cfg.K, cfg.d, cfg.T
+    ctx = make_context(cfg.schedule, d, K, seed=cfg.seed)
+    g = Denoiser.sdden_gmm_create(cfg.params.means, cfg.params.stds, cfg.params.logw, cfg.schedule.alpha_bar_state)
+    smp = DiffusionSampler(ctx, g, B)
+    b = smp.buf
+
+    ids = np.arange(B, dtype=np.int64)
+    y = as_f32_f64(philox.initial_state(cfg.seed, ids, d))
+    n = np.zeros(B, dtype=np.int64)
+    out_ref = np.zeros((B, d))
+    windows = mism = ties = 0
+    worst = 0.0
+    while n.size:
+        res, *_ = S.window(cfg.schedule, den, y, n, ids, K, seed=cfg.seed)
+        Bc = n.size
+        b.y[:Bc].copy_(f32(y)); b.n[:Bc].copy_(dev(n, torch.int32)); b.chain_id[:Bc].copy_(dev(ids, torch.int64))
+        smp.window(Bc)
+        nb, nt = decisions_match(host(b.adv)[:Bc], res)
+        mism += nb; ties += nt
+        same = host(b.adv)[:Bc] == res.adv
+        worst = max(worst, rel_err(host(b.y_out)[:Bc][same], res.y_out[same]))
+        y, n, ids = S.advance(T, as_f32_f64(res.y_out), res.adv, n, ids, out_ref)
+        windows += 1
+    print(f"[c1 replay] {windows} windows, decision mismatches {mism} (near ties {ties}), worst rel err {worst:.2e}")
+    assert mism == ties and worst < 5 * TOL
+
+    out, counters = smp.run(torch.arange(B, dtype=torch.int64, device="cuda"))
+    ref, st = S.sample(cfg.schedule, den, B, d, K, seed=cfg.seed)
+    got = host(out)
+    err = np.max(np.abs(got - ref) / np.maximum(1.0, np.abs(ref).max(axis=1, keepdims=True)), axis=1)
+    diverged = int((err > 1e-3).sum())
+    print(f"[c1 free run] GPU counters {counters}, oracle steps {st.steps} windows {st.chain_windows} "
+          f"rejections {st.rejections}; chains off the oracle path: {diverged}")
+    assert counters[0] == B * T
+    assert diverged <= 2                                   # a flipped near-tie moves a whole chain
+    if diverged == 0:
+        assert counters[1] == st.chain_windows and counters[2] == st.rejections
+
+
+def test_batch_composition_does_not_change_results():
+    from paper_2501_05370_amd.binding import Denoiser
+    from paper_2501_05370_amd.sampler import DiffusionSampler
+    cfg = W.make_config("c2", B=256, T=40)
+    ctx = make_context(cfg.schedule, cfg.d, cfg.K, seed=3)
+    g = Denoiser.sdden_gmm_create(cfg.params.means, cfg.params.stds, cfg.params.logw, cfg.schedule.alpha_bar_state)
+    smp = DiffusionSampler(ctx, g, 256)
+    full = host(smp.run(torch.arange(256, dtype=torch.int64, device="cuda"))[0]).copy()
+    sub_ids = torch.tensor([200, 3, 77, 255, 128], dtype=torch.int64, device="cuda")
+    smp2 = DiffusionSampler(ctx, g, 5, out_rows=256)
+    sub = host(smp2.run(sub_ids)[0])
+    assert np.array_equal(sub[[200, 3, 77, 255, 128]], full[[200, 3, 77, 255, 128]])
+
+
+@pytest.mark.parametrize("B,d,M,K,T", [(64, 1000, 16, 16, 40), (40, 10, 3, 5, 12), (32, 1003, 16, 16, 30),
+                                       (16, 2100, 7, 8, 20), (8, 4096, 16, 4, 9)])
+def test_langevin_window_matches_oracle(B, d, M, K, T):
+    rng = np.random.default_rng(8)
+    cfg = W.make_config("c5", B=B, d=d, M=M, K=K, T=T)
+    p = cfg.params
+    sc = GMMScore(p)
+    gamma = cfg.gamma
+    ctx = make_context(cfg.schedule, d, K, seed=21)
+    # start near / between components so that gradients differ along the window
+    comp = rng.integers(0, M, size=B)
+    x = as_f32_f64(p.means[comp] * rng.uniform(0.3, 1.0, size=(B, 1)) + rng.standard_normal((B, d)))
+    n = rng.integers(0, T, size=B)
+    n[:3] = [T - 1, T - 2, 0]
+    ids = rng.permutation(1000)[:B].astype(np.int64)
+    xo, adv, rej, lr, lu = L.ula_window(sc, x, n, ids, K, T, gamma, seed=21)
+    gx = torch.full((B, d), 9.0, dtype=torch.float32, device="cuda")
+    gadv = torch.zeros(B, dtype=torch.int32, device="cuda")
+    grej = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    glr = torch.full((B, K), 5.0, dtype=torch.float32, device="cuda")
+    glu = torch.full((B, K), 5.0, dtype=torch.float32, device="cuda")
+    ctx.sd_langevin_window(B, f32(x), dev(n, torch.int32), dev(ids, torch.int64), f32(p.means), f32(p.logw),
+                           float(p.stds[0, 0]), M, gamma, gx, gadv, grej, glr, glu)
+
+    class R:  # the fields decisions_match reads
+        pass
+    R.adv, R.logu, R.logratio = adv, lu, lr
+    nbad, near = decisions_match(host(gadv), R)
+    print(f"[langevin d={d}] rejected {rej.mean():.2f}, mean adv {adv.mean():.2f}, mismatches {nbad} (near ties {near})")
+    assert nbad == near
+    same = host(gadv) == adv
+    assert np.array_equal(host(grej)[same].astype(bool), rej[same])
+    assert rel_err(host(gx)[same], xo[same]) < TOL
+    # diagnostics are reported up to the position that stopped the window, 0 after it
+    for b in np.nonzero(same)[0]:
+        a = adv[b]
+        assert np.max(np.abs(host(glu)[b, :a] - lu[b, :a])) < 1e-5
+        assert np.max(np.abs(host(glr)[b, :a] - lr[b, :a]) / np.maximum(1, np.abs(lr[b, :a]))) < 1e-5
+        assert np.all(host(glr)[b, a:] == 0) and np.all(host(glu)[b, a:] == 0)
+
+
+def test_langevin_free_run_small():
+    from paper_2501_05370_amd.sampler import LangevinSampler
+    cfg = W.make_config("c5", B=48, d=200, M=4, K=8, T=60)
+    p = cfg.params
+    ctx = make_context(cfg.schedule, cfg.d, cfg.K, seed=5)
+    smp = LangevinSampler(ctx, f32(p.means), f32(p.logw), float(p.stds[0, 0]), cfg.gamma, cfg.B)
+    out, counters = smp.run(torch.arange(cfg.B, dtype=torch.int64, device="cuda"))
+    ref, cw, rejections = L.ula_sample(GMMScore(p), cfg.B, cfg.d, cfg.K, cfg.T, cfg.gamma, seed=5)
+    err = np.max(np.abs(host(out) - ref), axis=1) / np.maximum(1.0, np.abs(ref).max(axis=1))
+    diverged = int((err > 1e-3).sum())
+    print(f"[langevin free run] counters {counters}, oracle chain-windows {cw} rejections {rejections}, off-path {diverged}")
+    assert counters[0] == cfg.B * cfg.T and diverged <= 1
+    if diverged == 0:
+        assert counters[1] == cw and counters[2] == rejections
