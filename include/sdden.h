@@ -39,19 +39,27 @@ int sdden_lowrank_create(int32_t d, int32_t r, const float* mu, const float* U, 
 /* W1 [(d+E),H], W2 [H,H], W3 [H,d]: bf16 bit patterns, row = input feature; b1,b2 [H], b3 [d]:
  * host.  Time embedding of width E: emb[i] = sin(k w_i), emb[E/2+i] = cos(k w_i),
  * w_i = 10000^(-2i/E); its product with the last E rows of W1 is folded into a per-step bias
- * table at create time.  Rmax = largest R sdden_eval will see (sizes the hidden activations). */
+ * table at create time.  Rmax: rows reserved right away (as by sdden_reserve).
+ * d and H must be multiples of 128. */
 int sdden_mlp_create(int32_t d, int32_t H, int32_t E, const uint16_t* W1, const float* b1,
                      const uint16_t* W2, const float* b2, const uint16_t* W3, const float* b3,
                      int32_t T, int32_t Rmax, sdden** out);
 
+/* Setup call: allocate the per-call scratch (row lists, intermediate activations) that
+ * evaluations of up to Rmax rows need.  The gmm denoiser needs none; lowrank and mlp return
+ * SD_ERR_WORKSPACE from sdden_eval when R exceeds what was reserved.  May be called again with a
+ * larger Rmax (not while evaluations are in flight). */
+int sdden_reserve(sdden* den, int32_t Rmax);
+
 /* out[r] = D(X[r], krow[r]) for every r < R with krow[r] >= 0.
- * X [R,d], krow [R], out [R,d]: dev; X and out must not overlap.
- * Optional `count`: dev int32 or NULL; when given only rows r < min(R, *count * rows_per_chain)
- * are evaluated (matches sd_set_active_count; rows_per_chain = R / B of the call that sized R). */
+ * X [R,d], krow [R], out [R,d]: dev, 16-byte aligned; X and out must not overlap.
+ * Enqueues kernels on `stream` only: no allocation, no synchronisation. */
 int sdden_eval(sdden* den, int32_t R, const float* X, const int32_t* krow, float* out,
                void* stream);
 
-/* Restrict evaluation to the first (*count) * rows_per_chain rows; NULL removes the limit. */
+/* Optional device-resident row limit: when `count` (dev int32) is set, only rows
+ * r < min(R, *count * rows_per_chain) are evaluated, which lets a fixed launch sequence follow
+ * the batch as sd_advance shrinks it (see sd_set_active_count).  NULL removes the limit. */
 int sdden_set_active_count(sdden* den, const int32_t* count /*dev*/, int32_t rows_per_chain);
 
 int sdden_destroy(sdden* den);

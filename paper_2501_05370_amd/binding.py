@@ -56,6 +56,7 @@ _SIGNATURES = {
                                      POINTER(c_void_p)]),
     "sdden_mlp_create": (c_int, [c_int32, c_int32, c_int32] + [c_void_p] * 6 + [c_int32, c_int32,
                                                                                POINTER(c_void_p)]),
+    "sdden_reserve": (c_int, [c_void_p, c_int32]),
     "sdden_eval": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]),
     "sdden_set_active_count": (c_int, [c_void_p, c_void_p, c_int32]),
     "sdden_destroy": (c_int, [c_void_p]),
@@ -267,6 +268,9 @@ class Denoiser:
                 raise SDError(f"{nm}: need a contiguous {dt} CUDA tensor")
         self._check(self._lib.sdden_eval(self._h, R, X.data_ptr(), krow.data_ptr(), out.data_ptr(), _stream()),
                     "sdden_eval")
+
+    def sdden_reserve(self, Rmax: int):
+        self._check(self._lib.sdden_reserve(self._h, Rmax), "sdden_reserve")
 
     def sdden_set_active_count(self, count: Optional[torch.Tensor], rows_per_chain: int = 1):
         self._keep_count = count

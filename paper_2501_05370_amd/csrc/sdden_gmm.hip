@@ -173,6 +173,12 @@ int sdden_eval(sdden* den, int32_t R, const float* X, const int32_t* krow, float
   return den->eval(R, X, krow, out, static_cast<hipStream_t>(stream));
 }
 
+int sdden_reserve(sdden* den, int32_t Rmax) {
+  if (!den) return SD_ERR_ARG;
+  if (Rmax <= 0) return sdi::fail(den->err, SD_ERR_ARG, "sdden_reserve: Rmax must be > 0");
+  return den->reserve(Rmax);
+}
+
 int sdden_set_active_count(sdden* den, const int32_t* count, int32_t rows_per_chain) {
   if (!den) return SD_ERR_ARG;
   if (count && rows_per_chain <= 0) return sdi::fail(den->err, SD_ERR_ARG, "sdden_set_active_count: rows_per_chain must be > 0");

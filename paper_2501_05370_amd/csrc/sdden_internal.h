@@ -12,6 +12,8 @@ struct sdden {
   virtual ~sdden() {}
   // Enqueue out[r] = D(X[r], krow[r]) for rows r < R with krow[r] >= 0.
   virtual int eval(int R, const float* X, const int32_t* krow, float* out, hipStream_t st) = 0;
+  // Allocate whatever per-call scratch evaluations of up to R rows need (setup time only).
+  virtual int reserve(int R) { (void)R; return SD_OK; }
   int d = 0, T = 0;
   const int32_t* active = nullptr;   // optional device-side chain count
   int rows_per_chain = 1;

@@ -1,0 +1,353 @@
+// Random-init time-conditioned MLP denoiser: [x ; sinusoidal(k)] -> H -> H -> d, SiLU, bf16 weights
+// and activations, fp32 accumulation on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16).
+// All rows of a batched target call (every drafted state of every chain, each at its own step k)
+// go through three GEMMs (paper: Alg. "Speculative Sampling for DDM", (Par.) line; Sec. 3.1 for the
+// network as a black box).
+//
+// Data flow per call:
+//   compact_rows      rows with krow >= 0 -> dense list (masked drafts cost no MFMA work)
+//   gather_convert    X[rowidx[m]] fp32 -> Xb[m] bf16 (dense A operand of layer 1)
+//   gemm<1>           H1 = silu(Xb W1x + tb[krow])        tb[k] = b1 + emb(k) W1t, folded at create
+//   gemm<2>           H2 = silu(H1 W2 + b2)
+//   gemm<3>           out[rowidx[m]] = H2 W3 + b3          (fp32, scattered back to the source rows)
+//
+// GEMM kernel: C[M,N] = A[M,K] Bt[N,K]^T, both operands K-contiguous bf16.  Workgroup tile
+// BM x BN x 64 with 4 wavefronts (2x2), each wavefront (BM/2)x(BN/2) as 32x32 MFMA tiles.  LDS rows
+// are padded to 72 elements so the 16-byte fragment reads of 8 consecutive lanes cover all 32 banks.
+// The next K-slice is fetched into registers while the current one feeds the MFMAs.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "sdden_internal.h"
+#include "sdden_rows.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int BK = 64;
+constexpr int LDSK = BK + 8;      // padded LDS row, in bf16 elements
+
+struct MlpGemmArgs {
+  const uint16_t* A;     // [M, Kdim] bf16, dense
+  const uint16_t* Bt;    // [N, Kdim] bf16 (weights, transposed: row = output feature)
+  int N, Kdim;
+  const int32_t* count;  // device: M
+  const int32_t* rowidx; // dense row -> source row
+  const int32_t* krow;   // source row -> chain step
+  const float* bias;     // EPI 1: tb [T, N]; EPI 2, 3: b [N]
+  uint16_t* outb;        // EPI 1, 2: bf16 [M, N] dense
+  float* outf;           // EPI 3: fp32 [*, N] at source rows
+};
+
+__device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x)); }
+
+__device__ __forceinline__ uint16_t to_bf16_bits(float x) {
+  const __bf16 b = static_cast<__bf16>(x);
+  uint16_t u;
+  __builtin_memcpy(&u, &b, 2);
+  return u;
+}
+
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(kThreads) void mlp_gemm_kernel(MlpGemmArgs p) {
+  constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 MFMA tiles per wavefront, per dimension
+  constexpr int ACH = BM * (BK / 8) / kThreads;      // 16-byte chunks of A per thread per K-slice
+  constexpr int BCH = BN * (BK / 8) / kThreads;
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);              // [2][BM][LDSK]
+  uint16_t* Bs = As + 2 * BM * LDSK;                             // [2][BN][LDSK]
+
+  const int M = *p.count;
+  const int tiles_n = p.N / BN;
+  // Tiles sharing a row panel of A are adjacent, 8 row panels form a group that sweeps N together.
+  constexpr int GROUP = 8;
+  const int tiles_m_all = gridDim.x / tiles_n;
+  const int per_group = GROUP * tiles_n;
+  const int group = blockIdx.x / per_group;
+  const int first_m = group * GROUP;
+  const int gsize = min(GROUP, tiles_m_all - first_m);
+  const int in_group = blockIdx.x % per_group;
+  const int tile_m = first_m + in_group % gsize;
+  const int tile_n = in_group / gsize;
+  if (tile_m * BM >= M) return;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int half = lane >> 5, l32 = lane & 31;
+
+  const uint16_t* a_src[ACH];
+  const uint16_t* b_src[BCH];
+  int a_dst[ACH], b_dst[BCH];
+#pragma unroll
+  for (int i = 0; i < ACH; ++i) {
+    const int idx = t + kThreads * i;
+    const int row = idx >> 3, ch = idx & 7;
+    const int gm = min(tile_m * BM + row, M - 1);                // rows past M are loaded but never stored
+    a_src[i] = p.A + static_cast<int64_t>(gm) * p.Kdim + 8 * ch;
+    a_dst[i] = row * LDSK + 8 * ch;
+  }
+#pragma unroll
+  for (int i = 0; i < BCH; ++i) {
+    const int idx = t + kThreads * i;
+    const int row = idx >> 3, ch = idx & 7;
+    b_src[i] = p.Bt + static_cast<int64_t>(tile_n * BN + row) * p.Kdim + 8 * ch;
+    b_dst[i] = row * LDSK + 8 * ch;
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  uint4 ra[ACH], rb[BCH];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_src[i] + k0);
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_src[i] + k0);
+  };
+  auto stash = [&](int s) {
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) *reinterpret_cast<uint4*>(As + s * BM * LDSK + a_dst[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) *reinterpret_cast<uint4*>(Bs + s * BN * LDSK + b_dst[i]) = rb[i];
+  };
+
+  const int nk = p.Kdim / BK;
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int s = kt & 1;
+    if (kt + 1 < nk) fetch((kt + 1) * BK);
+    const uint16_t* Aw = As + s * BM * LDSK + (wm * (BM / 2) + l32) * LDSK + 8 * half;
+    const uint16_t* Bw = Bs + s * BN * LDSK + (wn * (BN / 2) + l32) * LDSK + 8 * half;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8 a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const uint4 u = *reinterpret_cast<const uint4*>(Aw + i * 32 * LDSK + kk);
+        __builtin_memcpy(&a[i], &u, 16);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const uint4 u = *reinterpret_cast<const uint4*>(Bw + j * 32 * LDSK + kk);
+        __builtin_memcpy(&b[j], &u, 16);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) stash(s ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: element (row = (v/4)*8 + half*4 + v%4, col = l32) of each 32x32 tile
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int gm = tile_m * BM + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+      if (gm >= M) continue;
+      const int src = p.rowidx[gm];
+      const float* brow = EPI == 1 ? p.bias + static_cast<int64_t>(p.krow[src]) * p.N : p.bias;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int gn = tile_n * BN + wn * (BN / 2) + j * 32 + l32;
+        const float c = acc[i][j][v] + brow[gn];
+        if (EPI == 3) p.outf[static_cast<int64_t>(src) * p.N + gn] = c;
+        else p.outb[static_cast<int64_t>(gm) * p.N + gn] = to_bf16_bits(silu(c));
+      }
+    }
+  }
+}
+
+// X[rowidx[m], :] fp32 -> Xb[m, :] bf16, 8 elements per thread.
+__global__ __launch_bounds__(kThreads) void gather_convert_kernel(const float* __restrict__ X,
+                                                                  const int32_t* __restrict__ rowidx,
+                                                                  const int32_t* __restrict__ count,
+                                                                  uint16_t* __restrict__ Xb, int d) {
+  const int M = *count;
+  const int per_row = d / 8;
+  for (int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+       g < static_cast<int64_t>(M) * per_row; g += static_cast<int64_t>(gridDim.x) * kThreads) {
+    const int m = static_cast<int>(g / per_row), c = static_cast<int>(g % per_row);
+    const float* src = X + static_cast<int64_t>(rowidx[m]) * d + 8 * c;
+    const float4 lo = *reinterpret_cast<const float4*>(src);
+    const float4 hi = *reinterpret_cast<const float4*>(src + 4);
+    uint4 o;
+    o.x = to_bf16_bits(lo.x) | (static_cast<uint32_t>(to_bf16_bits(lo.y)) << 16);
+    o.y = to_bf16_bits(lo.z) | (static_cast<uint32_t>(to_bf16_bits(lo.w)) << 16);
+    o.z = to_bf16_bits(hi.x) | (static_cast<uint32_t>(to_bf16_bits(hi.y)) << 16);
+    o.w = to_bf16_bits(hi.z) | (static_cast<uint32_t>(to_bf16_bits(hi.w)) << 16);
+    *reinterpret_cast<uint4*>(Xb + static_cast<int64_t>(m) * d + 8 * c) = o;
+  }
+}
+
+float bf16_bits_to_float(uint16_t b) {
+  const uint32_t u = static_cast<uint32_t>(b) << 16;
+  float f;
+  std::memcpy(&f, &u, 4);
+  return f;
+}
+
+template <int BM, int BN, int EPI>
+int launch_gemm(const MlpGemmArgs& a, int Rmax, hipStream_t st, std::string& err) {
+  constexpr size_t shmem = 2 * static_cast<size_t>(BM + BN) * LDSK * sizeof(uint16_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    SD_HIP_TRY(err, hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_gemm_kernel<BM, BN, EPI>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem)));
+    attr_set = true;
+  }
+  const int tiles_m = (Rmax + BM - 1) / BM, tiles_n = a.N / BN;
+  hipLaunchKernelGGL((mlp_gemm_kernel<BM, BN, EPI>), dim3(tiles_m * tiles_n), dim3(kThreads), shmem, st, a);
+  return SD_OK;
+}
+
+struct MlpDenoiser final : sdden {
+  int H = 0, E = 0;
+  uint16_t *W1t = nullptr, *W2t = nullptr, *W3t = nullptr;    // [H,d], [H,H], [d,H] bf16
+  float *tb = nullptr, *b2 = nullptr, *b3 = nullptr;          // [T,H], [H], [d]
+  int32_t *rowidx = nullptr, *count = nullptr;
+  uint16_t *Xb = nullptr, *H1 = nullptr, *H2 = nullptr;
+  int cap_rows = 0;
+  int tile = 128;                                             // workgroup tile edge (128 or 256)
+
+  ~MlpDenoiser() override {
+    for (void* q : {static_cast<void*>(W1t), static_cast<void*>(W2t), static_cast<void*>(W3t), static_cast<void*>(tb),
+                    static_cast<void*>(b2), static_cast<void*>(b3), static_cast<void*>(rowidx), static_cast<void*>(count),
+                    static_cast<void*>(Xb), static_cast<void*>(H1), static_cast<void*>(H2)})
+      if (q) (void)hipFree(q);
+  }
+
+  int reserve(int R) override {
+    if (R <= cap_rows) return SD_OK;
+    for (void* q : {static_cast<void*>(rowidx), static_cast<void*>(Xb), static_cast<void*>(H1), static_cast<void*>(H2)})
+      if (q) (void)hipFree(q);
+    rowidx = nullptr; Xb = H1 = H2 = nullptr; cap_rows = 0;
+    SD_HIP_TRY(err, hipMalloc(&rowidx, sizeof(int32_t) * static_cast<size_t>(R)));
+    SD_HIP_TRY(err, hipMalloc(&Xb, 2 * static_cast<size_t>(R) * d));
+    SD_HIP_TRY(err, hipMalloc(&H1, 2 * static_cast<size_t>(R) * H));
+    SD_HIP_TRY(err, hipMalloc(&H2, 2 * static_cast<size_t>(R) * H));
+    if (!count) SD_HIP_TRY(err, hipMalloc(&count, sizeof(int32_t)));
+    cap_rows = R;
+    return SD_OK;
+  }
+
+  int eval(int R, const float* X, const int32_t* krow, float* out, hipStream_t st) override {
+    if (R > cap_rows)
+      return sdi::fail(err, SD_ERR_WORKSPACE, "sdden_eval(mlp): %d rows exceed the %d reserved (sdden_reserve)", R, cap_rows);
+    if (!sdi::aligned16(X)) return sdi::fail(err, SD_ERR_ARG, "sdden_eval(mlp): X must be 16-byte aligned");
+    hipLaunchKernelGGL(sdrows::compact_rows_kernel, dim3(1), dim3(sdrows::kScan), 0, st, krow, rowidx, count,
+                       active, rows_per_chain, R);
+    const int64_t chunks = static_cast<int64_t>(R) * (d / 8);
+    const int cgrid = static_cast<int>(std::min<int64_t>((chunks + kThreads - 1) / kThreads, 256 * 32));
+    hipLaunchKernelGGL(gather_convert_kernel, dim3(cgrid), dim3(kThreads), 0, st, X, rowidx, count, Xb, d);
+    MlpGemmArgs a;
+    a.count = count; a.rowidx = rowidx; a.krow = krow;
+    int rc;
+    a.A = Xb; a.Bt = W1t; a.N = H; a.Kdim = d; a.bias = tb; a.outb = H1; a.outf = nullptr;
+    rc = tile == 256 ? launch_gemm<256, 256, 1>(a, R, st, err) : launch_gemm<128, 128, 1>(a, R, st, err);
+    if (rc) return rc;
+    a.A = H1; a.Bt = W2t; a.N = H; a.Kdim = H; a.bias = b2; a.outb = H2;
+    rc = tile == 256 ? launch_gemm<256, 256, 2>(a, R, st, err) : launch_gemm<128, 128, 2>(a, R, st, err);
+    if (rc) return rc;
+    a.A = H2; a.Bt = W3t; a.N = d; a.Kdim = H; a.bias = b3; a.outb = nullptr; a.outf = out;
+    rc = tile == 256 ? launch_gemm<256, 256, 3>(a, R, st, err) : launch_gemm<128, 128, 3>(a, R, st, err);
+    if (rc) return rc;
+    SD_HIP_TRY(err, hipGetLastError());
+    return SD_OK;
+  }
+};
+
+// dst[n][k] = src[k][n] for a [K, N] bf16 matrix.
+void transpose_bits(const uint16_t* src, int K, int N, std::vector<uint16_t>& dst) {
+  dst.resize(static_cast<size_t>(K) * N);
+  constexpr int TB = 64;
+  for (int k0 = 0; k0 < K; k0 += TB)
+    for (int n0 = 0; n0 < N; n0 += TB)
+      for (int k = k0; k < std::min(K, k0 + TB); ++k)
+        for (int n = n0; n < std::min(N, n0 + TB); ++n)
+          dst[static_cast<size_t>(n) * K + k] = src[static_cast<size_t>(k) * N + n];
+}
+
+}  // namespace
+
+extern "C" int sdden_mlp_create(int32_t d, int32_t H, int32_t E, const uint16_t* W1, const float* b1,
+                                const uint16_t* W2, const float* b2, const uint16_t* W3, const float* b3,
+                                int32_t T, int32_t Rmax, sdden** out) {
+  std::string& ER = sdi::g_den_create_error;
+  if (!W1 || !b1 || !W2 || !b2 || !W3 || !b3 || !out || d <= 0 || H <= 0 || E < 0 || (E & 1) || T <= 0 || Rmax <= 0)
+    return sdi::fail(ER, SD_ERR_ARG, "sdden_mlp_create: bad argument");
+  if (d % 128 != 0 || H % 128 != 0)
+    return sdi::fail(ER, SD_ERR_UNSUPPORTED, "sdden_mlp_create: d=%d and H=%d must be multiples of 128", d, H);
+  MlpDenoiser* m = new (std::nothrow) MlpDenoiser;
+  if (!m) return sdi::fail(ER, SD_ERR_ARG, "sdden_mlp_create: out of host memory");
+  m->d = d; m->T = T; m->H = H; m->E = E;
+  m->tile = (d % 256 == 0 && H % 256 == 0) ? 256 : 128;
+  if (const char* env = std::getenv("SDDEN_MLP_TILE")) {
+    const int v = std::atoi(env);
+    if (v == 128 || (v == 256 && m->tile == 256)) m->tile = v;
+  }
+  // per-step bias table: tb[k] = b1 + emb(k) . W1[d:d+E, :],  emb = [sin(k w_i) ; cos(k w_i)], w_i = 10000^(-2i/E)
+  std::vector<float> tb(static_cast<size_t>(T) * H);
+  {
+    const int half = E / 2;
+    std::vector<double> emb(E > 0 ? E : 1), row(H);
+    for (int k = 0; k < T; ++k) {
+      for (int i = 0; i < half; ++i) {
+        const double w = std::pow(10000.0, -static_cast<double>(i) / half);
+        emb[i] = std::sin(k * w);
+        emb[half + i] = std::cos(k * w);
+      }
+      for (int n = 0; n < H; ++n) row[n] = b1[n];
+      for (int e = 0; e < E; ++e) {
+        const uint16_t* wrow = W1 + static_cast<size_t>(d + e) * H;
+        const double ev = emb[e];
+        for (int n = 0; n < H; ++n) row[n] += ev * bf16_bits_to_float(wrow[n]);
+      }
+      for (int n = 0; n < H; ++n) tb[static_cast<size_t>(k) * H + n] = static_cast<float>(row[n]);
+    }
+  }
+  std::vector<uint16_t> w1t, w2t, w3t;
+  transpose_bits(W1, d, H, w1t);      // first d rows of W1 only: [d,H] -> [H,d]
+  transpose_bits(W2, H, H, w2t);
+  transpose_bits(W3, H, d, w3t);      // [H,d] -> [d,H]
+  hipError_t e = hipSuccess;
+  auto up = [&](auto** dst, const void* src, size_t bytes) {
+    if (e != hipSuccess) return;
+    e = hipMalloc(reinterpret_cast<void**>(dst), bytes);
+    if (e == hipSuccess) e = hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice);
+  };
+  up(&m->W1t, w1t.data(), w1t.size() * 2);
+  up(&m->W2t, w2t.data(), w2t.size() * 2);
+  up(&m->W3t, w3t.data(), w3t.size() * 2);
+  up(&m->tb, tb.data(), tb.size() * 4);
+  up(&m->b2, b2, static_cast<size_t>(H) * 4);
+  up(&m->b3, b3, static_cast<size_t>(d) * 4);
+  if (e != hipSuccess) {
+    delete m;
+    return sdi::fail(ER, SD_ERR_HIP, "sdden_mlp_create: %s", hipGetErrorString(e));
+  }
+  if (int rc = m->reserve(Rmax)) {
+    ER = m->err;
+    delete m;
+    return rc;
+  }
+  *out = m;
+  return SD_OK;
+}

@@ -1,0 +1,39 @@
+"""Glue from a ``workloads.Config`` to the library objects that run it (no arithmetic)."""
+from __future__ import annotations
+
+import torch
+
+from .binding import Context, Denoiser
+from .sampler import DiffusionSampler, LangevinSampler
+
+
+def make_context(cfg, seed=None) -> Context:
+    s = cfg.schedule
+    ctx = Context(s.a, s.c, s.sigma, cfg.d, cfg.K)
+    ctx.sd_set_seed(cfg.seed if seed is None else seed)
+    return ctx
+
+
+def make_denoiser(cfg, max_rows: int) -> Denoiser:
+    p, s = cfg.params, cfg.schedule
+    if cfg.kind == "gmm":
+        return Denoiser.sdden_gmm_create(p.means, p.stds, p.logw, s.alpha_bar_state)
+    if cfg.kind == "lowrank":
+        den = Denoiser.sdden_lowrank_create(p.mu, p.U, p.s2, s.alpha_bar_state)
+        den.sdden_reserve(max_rows)
+        return den
+    if cfg.kind == "mlp":
+        return Denoiser.sdden_mlp_create(p, cfg.T, max_rows)
+    raise ValueError(f"no denoiser for workload kind {cfg.kind!r}")
+
+
+def make_sampler(cfg, B=None, out_rows=None, seed=None):
+    """A sampler for up to B chains of configuration ``cfg`` on the current device."""
+    B = cfg.B if B is None else B
+    ctx = make_context(cfg, seed)
+    if cfg.kind == "langevin":
+        p = cfg.params
+        dev = lambda a: torch.as_tensor(a, dtype=torch.float32).cuda().contiguous()
+        return LangevinSampler(ctx, dev(p.means), dev(p.logw), float(p.stds[0, 0]), cfg.gamma, B, out_rows)
+    den = make_denoiser(cfg, B * cfg.K)
+    return DiffusionSampler(ctx, den, B, out_rows)
