@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-sampling hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1..c5] [--stages]
+
+A *step* is one complete pass of the sampler over the batch of the chosen workload: every chain
+is initialised and taken from step 0 to step T through windows of [window-start prediction ->
+draft rollout -> batched target evaluation of all drafted states -> accept / first-reject /
+reflect -> advance + compaction].  All inputs (schedule, denoiser parameters, chain ids) are
+resident in HBM before the timed region.  The metric is verified diffusion steps per second,
+B*T*steps / time.  One JSON line is printed; it also carries
+
+* ``roofline``      the dominant kernel of the workload: algorithmic bytes / flops per launch over
+                    its mean launch duration measured with HIP events inside the timed region;
+* ``cpu_baseline``  the fp64 oracle (``oracle/``) timed on the host on a bounded sample of the
+                    same workload -- a reported baseline, not a target;
+* ``mean_accepted_draft_length`` and the per-window counters.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+DEFAULT_WORKLOAD = "c4"
+
+DESCRIPTIONS = {
+    "c1": "c1: toy DDPM d=2, 64 chains, ring GMM posterior mean, linear beta T=100, K=4",
+    "c2": "c2: GMM DDPM d=64, 4096 chains, 32-component posterior mean, cosine T=200, K=8",
+    "c3": "c3: linear-Gaussian DDPM d=3072, 2048 chains, rank-256 Woodbury denoiser (fp32 MFMA), cosine T=250, K=10",
+    "c4": "c4: MLP DDPM d=12288, 512 chains, 3-layer width-4096 SiLU MLP (bf16 MFMA), linear T=500, K=16",
+    "c5": "c5: speculative ULA d=1000, 16384 chains, 16-component GMM score, gamma=1e-2, T=2000, K=16",
+}
+
+# published MI355X peaks used as roofline denominators
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "mfma_fp32": (157.3, "TFLOP/s"),
+        "alu_fp64": (78.6, "TFLOP/s"), "alu_fp32": (157.3, "TFLOP/s")}
+
+
+def roofline_plan(cfg):
+    """Which kernel is reported for a workload, how it is timed and its algorithmic work.
+
+    Returns dict(kernel, stage or den_which, bound, peak key, work(counters) -> total units)."""
+    d, K = cfg.d, cfg.K
+    if cfg.kind == "mlp":
+        H = cfg.params.H
+        return dict(kernel="mlp_gemm_kernel<256,256,1> (layer 1: rows x 12288 x 4096, bf16 MFMA)", den_which=1,
+                    bound="mfma", peak="mfma_bf16", scale=1e-12,
+                    work=lambda c: 2.0 * c[4] * d * H)                 # rows evaluated = sum Kt
+    if cfg.kind == "lowrank":
+        rpad = -(-cfg.params.U.shape[1] // 16) * 16
+        return dict(kernel="lowrank_gemm_kernel<2> (P' Q^T + epilogue, fp32 MFMA)", den_which=2,
+                    bound="mfma", peak="mfma_fp32", scale=1e-12,
+                    work=lambda c: 2.0 * c[4] * d * rpad)
+    if cfg.kind == "gmm":
+        # verify/reflect: pass 1 reads y, D0, Kt drafts, Kt-1 predictions; pass 2 re-reads 4 rows and
+        # writes 1 on a rejection, else copies 1 row
+        return dict(kernel="verify_kernel (accept / first-reject / reflect)", stage="verify",
+                    bound="hbm", peak="hbm", scale=1e-9,
+                    work=lambda c: 4.0 * d * ((2 * c[4] + c[1]) + 5 * c[2] + 2 * (c[1] - c[2])))
+    if cfg.kind == "langevin":
+        M = cfg.params.means.shape[0]
+        # fp64 flops per evaluated position: logits 3 M d, gradient 2 M d + 2 d, Delta / dots / update 12 d
+        return dict(kernel="langevin_window_kernel (fused draft + score + verify)", stage="langevin_window",
+                    bound="alu", peak="alu_fp64", scale=1e-12,
+                    work=lambda c: float(c[0] + c[1]) * d * (5.0 * M + 14.0))
+    raise ValueError(cfg.kind)
+
+
+def run_gpu(cfg, steps, warmup, stages):
+    import torch
+    from paper_2501_05370_amd.runner import make_sampler
+    from paper_2501_05370_amd.sampler import StageTimer
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (the HIP library has no CPU fallback)")
+    torch.cuda.set_device(0)
+    smp = make_sampler(cfg)
+    ids = torch.arange(cfg.B, dtype=torch.int64, device="cuda")
+    plan = roofline_plan(cfg)
+    for w in range(warmup):
+        smp.ctx.sd_set_seed(cfg.seed + 1000 + w)
+        smp.run(ids)
+    torch.cuda.synchronize()
+
+    den = getattr(smp, "den", None)
+    if stages:
+        smp.timer = StageTimer()
+    elif "stage" in plan:
+        smp.timer = StageTimer([plan["stage"]])
+    if "den_which" in plan:
+        den.sdden_profile(plan["den_which"])
+    smp.buf.counters.zero_()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        smp.ctx.sd_set_seed(cfg.seed + s)
+        smp.run(ids, reset_counters=False)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    counters = smp.buf.counters.tolist()
+    timed = smp.timer.collect() if hasattr(smp.timer, "collect") else {}
+    if "den_which" in plan:
+        k_ms, k_launches = den.sdden_profile_collect()
+        den.sdden_profile(0)
+    else:
+        k_ms, k_launches, _ = timed[plan["stage"]]
+    work = plan["work"](counters)
+    peak, unit = PEAK[plan["peak"]]
+    achieved = work * plan["scale"] / (k_ms * 1e-3) if k_ms > 0 else 0.0
+    roofline = {"kernel": plan["kernel"], "bound": plan["bound"], "achieved": round(achieved, 3), "peak": peak,
+                "unit": unit, "frac": round(achieved / peak, 5), "traffic": None,
+                "avg_launch_us": round(1e3 * k_ms / max(1, k_launches), 3), "launches": k_launches,
+                "work_per_launch": work / max(1, k_launches)}
+    stage_table = {k: {"ms_total": round(v[0], 3), "launches": v[1], "us_per_launch": round(1e3 * v[0] / max(1, v[1]), 2)}
+                   for k, v in timed.items()} if stages else None
+    return elapsed, counters, roofline, stage_table
+
+
+def cpu_baseline(cfg, budget_s=15.0):
+    """Time the oracle on a bounded sample of the workload: a subset of the chains, run window by
+    window until the time budget is used or the chains finish."""
+    import workloads as W
+    from oracle import langevin as L
+    from oracle import philox
+    from oracle import speculative as S
+    from oracle.denoisers import GMMDenoiser, GMMScore, LowRankDenoiser, MLPDenoiser
+    try:
+        from threadpoolctl import threadpool_info
+        blas_threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        blas_threads = 1
+    nchains = {"c1": 64, "c2": 256, "c3": 16, "c4": 4, "c5": 16}[cfg.name]
+    nchains = min(nchains, cfg.B)
+    ids = np.arange(nchains, dtype=np.int64)
+    sched = cfg.schedule
+    if cfg.kind == "gmm":
+        D, cores = GMMDenoiser(cfg.params, sched.alpha_bar_state), 1
+    elif cfg.kind == "lowrank":
+        D, cores = LowRankDenoiser(cfg.params, sched.alpha_bar_state), blas_threads
+    elif cfg.kind == "mlp":
+        D, cores = MLPDenoiser(cfg.params), blas_threads
+    else:
+        D, cores = GMMScore(cfg.params), 1
+    y = philox.initial_state(cfg.seed, ids, cfg.d)
+    n = np.zeros(nchains, dtype=np.int64)
+    out = np.zeros((nchains, cfg.d))
+    steps_done = windows = 0
+    t0 = time.perf_counter()
+    while n.size and time.perf_counter() - t0 < budget_s:
+        if cfg.kind == "langevin":
+            y_out, adv, _, _, _ = L.ula_window(D, y, n, ids, cfg.K, cfg.T, cfg.gamma, cfg.seed)
+        else:
+            res, *_ = S.window(sched, D, y, n, ids, cfg.K, cfg.seed)
+            y_out, adv = res.y_out, res.adv
+        steps_done += int(adv.sum())
+        windows += 1
+        y, n, ids = S.advance(cfg.T, y_out, adv, n, ids, out)
+    dt = time.perf_counter() - t0
+    return {"value": round(steps_done / dt, 3), "unit": "verified diffusion steps/s", "cores": cores,
+            "kind": "oracle",
+            "sample": f"{nchains} of {cfg.B} chains, {windows} windows from step 0 "
+                      f"({steps_done} verified steps in {dt:.1f} s; numpy fp64)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(DESCRIPTIONS))
+    ap.add_argument("--stages", action="store_true", help="time every stage (adds event overhead)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU only (chains are independent and would shard by "
+                         "chain id with no collective on the hot path); run with --gpus 1")
+    import workloads as W
+    cfg = W.make_config(args.workload)
+    steps = args.steps if args.steps is not None else {"c1": 20, "c2": 10, "c3": 3, "c4": 3, "c5": 2}[cfg.name]
+    elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages)
+    total_steps = counters[0]
+    assert total_steps == cfg.B * cfg.T * steps, (total_steps, cfg.B, cfg.T, steps)
+    line = {
+        "metric": "verified diffusion steps/sec at 1 GPU",
+        "value": round(total_steps / elapsed, 1),
+        "unit": "verified diffusion steps/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * elapsed / steps, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.kind == "mlp" else "f32", "data": "synthetic",
+        "config": {"workload": DESCRIPTIONS[cfg.name], "chains": cfg.B, "d": cfg.d, "window_K": cfg.K,
+                   "chain_steps_T": cfg.T, "drafter": "frozen", "seed": cfg.seed,
+                   "step_definition": "one full sampler pass: all chains from step 0 to T"},
+        "mean_accepted_draft_length": round(counters[0] / max(1, counters[1]), 4),
+        "windows_per_step": round(counters[3] / steps, 2),
+        "ms_per_window": round(1e3 * elapsed / max(1, counters[3]), 4),
+        "rejections_per_chain_window": round(counters[2] / max(1, counters[1]), 4),
+        "target_rows_evaluated": counters[4],
+        "roofline": roofline,
+    }
+    if stage_table:
+        line["stages"] = stage_table
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -126,8 +126,8 @@ int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const in
  * in place: y [B,d], n [B], chain_id [B] -- rewritten with the remaining chains        (dev)
  * out: out [*, d], row index = chain_id (caller sizes it); B_active: dev int32, number of
  *      remaining chains.  B_active may be the pointer given to sd_set_active_count.
- *      counters: dev int64[4] or NULL, accumulated: {sum adv, chains processed, rejections,
- *      windows}.  Needs the workspace. */
+ *      counters: dev int64[5] or NULL, accumulated: {sum adv, chains processed, rejections,
+ *      windows, sum Kt (positions drafted)}.  Needs the workspace. */
 int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv,
                const uint8_t* rejected, float* y, int32_t* n, int64_t* chain_id, float* out,
                int32_t* B_active, int64_t* counters, void* stream);

@@ -62,6 +62,14 @@ int sdden_eval(sdden* den, int32_t R, const float* X, const int32_t* krow, float
  * the batch as sd_advance shrinks it (see sd_set_active_count).  NULL removes the limit. */
 int sdden_set_active_count(sdden* den, const int32_t* count /*dev*/, int32_t rows_per_chain);
 
+/* Measurement aid: time the `which`-th kernel of every following sdden_eval with HIP events on
+ * the evaluation's stream (gmm: 1 = posterior mean; lowrank: 1, 2 = the two GEMMs; mlp: 1..3 = the
+ * three GEMMs; 0 = off, the default).  sdden_profile_collect waits for the recorded events, returns
+ * the summed kernel time in ms and the number of timed launches, and starts a new collection.
+ * Event objects are created on demand while profiling is on (never otherwise). */
+int sdden_profile(sdden* den, int32_t which);
+int sdden_profile_collect(sdden* den, double* total_ms, int64_t* launches);
+
 int sdden_destroy(sdden* den);
 const char* sdden_last_error(const sdden* den);
 

@@ -59,6 +59,8 @@ _SIGNATURES = {
     "sdden_reserve": (c_int, [c_void_p, c_int32]),
     "sdden_eval": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]),
     "sdden_set_active_count": (c_int, [c_void_p, c_void_p, c_int32]),
+    "sdden_profile": (c_int, [c_void_p, c_int32]),
+    "sdden_profile_collect": (c_int, [c_void_p, POINTER(ctypes.c_double), POINTER(c_int64)]),
     "sdden_destroy": (c_int, [c_void_p]),
     "sdden_last_error": (c_char_p, [c_void_p]),
 }
@@ -271,6 +273,15 @@ class Denoiser:
 
     def sdden_reserve(self, Rmax: int):
         self._check(self._lib.sdden_reserve(self._h, Rmax), "sdden_reserve")
+
+    def sdden_profile(self, which: int):
+        self._check(self._lib.sdden_profile(self._h, which), "sdden_profile")
+
+    def sdden_profile_collect(self):
+        ms, n = ctypes.c_double(), c_int64()
+        self._check(self._lib.sdden_profile_collect(self._h, ctypes.byref(ms), ctypes.byref(n)),
+                    "sdden_profile_collect")
+        return ms.value, n.value
 
     def sdden_set_active_count(self, count: Optional[torch.Tensor], rows_per_chain: int = 1):
         self._keep_count = count

@@ -378,7 +378,7 @@ constexpr int kScanBlock = 1024;
 __global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
     const int32_t* __restrict__ adv, const uint8_t* __restrict__ rej, int32_t* n, int64_t* chain_id,
     int32_t* __restrict__ dest, int64_t* __restrict__ outrow, int32_t* B_active, int64_t* counters,
-    const int32_t* active, int B, int T) {
+    const int32_t* active, int B, int T, int K) {
   __shared__ int wave_tot[kScanBlock / 64];
   __shared__ int sh_base;
   __shared__ long long sh_cnt[3];
@@ -386,7 +386,7 @@ __global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid == 0) { sh_base = 0; sh_cnt[0] = sh_cnt[1] = sh_cnt[2] = 0; }
   __syncthreads();
-  long long my_adv = 0, my_rej = 0;
+  long long my_adv = 0, my_rej = 0, my_kt = 0;
   for (int start = 0; start < Bact; start += kScanBlock) {
     const int b = start + tid;
     const bool in = b < Bact;
@@ -394,6 +394,7 @@ __global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
     int64_t id = 0;
     bool keep = false;
     if (in) {
+      my_kt += min(K, T - n[b]);
       nn = n[b] + adv[b];
       id = chain_id[b];
       keep = nn < T;
@@ -428,6 +429,7 @@ __global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
   if (counters) {
     atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[0]), static_cast<unsigned long long>(my_adv));
     atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[2]), static_cast<unsigned long long>(my_rej));
+    atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[1]), static_cast<unsigned long long>(my_kt));
   }
   __syncthreads();
   if (tid == 0) {
@@ -437,6 +439,7 @@ __global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
       counters[1] += Bact;
       counters[2] += sh_cnt[2];
       counters[3] += Bact > 0 ? 1 : 0;
+      counters[4] += sh_cnt[1];
     }
   }
 }
@@ -657,7 +660,7 @@ int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, c
     hipLaunchKernelGGL(fill_i32_kernel, dim3((B + 255) / 256), dim3(256), 0, st, dest, B, -2);
   }
   hipLaunchKernelGGL(advance_scan_kernel, dim3(1), dim3(kScanBlock), 0, st, adv, rejected, n, chain_id,
-                     dest, outrow, B_active, counters, ctx->active, B, ctx->T);
+                     dest, outrow, B_active, counters, ctx->active, B, ctx->T, ctx->K);
   if (B > 0) {
     const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y_out) && sdi::aligned16(y) && sdi::aligned16(out);
     const int ncol = vec ? ctx->d / 4 : ctx->d;

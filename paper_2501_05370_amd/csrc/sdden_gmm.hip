@@ -110,7 +110,9 @@ struct GmmDenoiser final : sdden {
     p.R = R; p.d = d; p.M = M;
     const size_t shmem = sizeof(double) * kRowsPerBlock * static_cast<size_t>(M + d);
     const unsigned grid = static_cast<unsigned>((R + kRowsPerBlock - 1) / kRowsPerBlock);
+    prof.mark(1, st);
     hipLaunchKernelGGL(gmm_posterior_mean_kernel, dim3(grid), dim3(64 * kRowsPerBlock), shmem, st, p);
+    prof.mark(1, st);
     SD_HIP_TRY(err, hipGetLastError());
     return SD_OK;
   }
@@ -177,6 +179,30 @@ int sdden_reserve(sdden* den, int32_t Rmax) {
   if (!den) return SD_ERR_ARG;
   if (Rmax <= 0) return sdi::fail(den->err, SD_ERR_ARG, "sdden_reserve: Rmax must be > 0");
   return den->reserve(Rmax);
+}
+
+int sdden_profile(sdden* den, int32_t which) {
+  if (!den || which < 0) return SD_ERR_ARG;
+  den->prof.which = which;
+  den->prof.used = 0;
+  return SD_OK;
+}
+
+int sdden_profile_collect(sdden* den, double* total_ms, int64_t* launches) {
+  if (!den || !total_ms || !launches) return SD_ERR_ARG;
+  sdden_profiler& pr = den->prof;
+  double tot = 0.0;
+  const size_t pairs = pr.used / 2;
+  if (pairs) SD_HIP_TRY(den->err, hipEventSynchronize(pr.events[2 * pairs - 1]));
+  for (size_t i = 0; i < pairs; ++i) {
+    float ms = 0.f;
+    SD_HIP_TRY(den->err, hipEventElapsedTime(&ms, pr.events[2 * i], pr.events[2 * i + 1]));
+    tot += ms;
+  }
+  *total_ms = tot;
+  *launches = static_cast<int64_t>(pairs);
+  pr.used = 0;
+  return SD_OK;
 }
 
 int sdden_set_active_count(sdden* den, const int32_t* count, int32_t rows_per_chain) {

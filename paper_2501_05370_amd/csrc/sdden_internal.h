@@ -4,9 +4,29 @@
 
 #include <cstdint>
 #include <string>
+#include <vector>
 
 #include "../../include/sdden.h"
 #include "sd_internal.h"
+
+// HIP-event timing of one chosen kernel inside sdden_eval (measurement only; off by default).
+struct sdden_profiler {
+  int which = 0;                       // 0 = off, else the 1-based index of the timed kernel
+  std::vector<hipEvent_t> events;      // start/stop pairs, reused between collections
+  size_t used = 0;
+  ~sdden_profiler() {
+    for (hipEvent_t e : events) (void)hipEventDestroy(e);
+  }
+  void mark(int kernel_index, hipStream_t st) {
+    if (which != kernel_index) return;
+    if (used == events.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return;
+      events.push_back(e);
+    }
+    (void)hipEventRecord(events[used++], st);
+  }
+};
 
 struct sdden {
   virtual ~sdden() {}
@@ -15,6 +35,7 @@ struct sdden {
   // Allocate whatever per-call scratch evaluations of up to R rows need (setup time only).
   virtual int reserve(int R) { (void)R; return SD_OK; }
   int d = 0, T = 0;
+  sdden_profiler prof;
   const int32_t* active = nullptr;   // optional device-side chain count
   int rows_per_chain = 1;
   std::string err;

@@ -235,10 +235,14 @@ struct LowRankDenoiser final : sdden {
     const int tiles_m = (R + BM - 1) / BM;
     // stage 1: P' = gain .* (X Q - sab qmu)       [M, rpad]
     a.A = X; a.lda = d; a.Bm = Q; a.N = rpad; a.Kdim = d; a.a_gather = 1; a.out = P;
+    prof.mark(1, st);
     hipLaunchKernelGGL(lowrank_gemm_kernel<1>, dim3(tiles_m * ((rpad + BN - 1) / BN)), dim3(kThreads), 0, st, a);
+    prof.mark(1, st);
     // stage 2: out = P' Q^T + gperp x + coef mu   [rows, d]
     a.A = P; a.lda = rpad; a.Bm = QT; a.N = d; a.Kdim = rpad; a.a_gather = 0; a.out = out;
+    prof.mark(2, st);
     hipLaunchKernelGGL(lowrank_gemm_kernel<2>, dim3(tiles_m * ((d + BN - 1) / BN)), dim3(kThreads), 0, st, a);
+    prof.mark(2, st);
     SD_HIP_TRY(err, hipGetLastError());
     return SD_OK;
   }

@@ -261,13 +261,19 @@ struct MlpDenoiser final : sdden {
     a.count = count; a.rowidx = rowidx; a.krow = krow;
     int rc;
     a.A = Xb; a.Bt = W1t; a.N = H; a.Kdim = d; a.bias = tb; a.outb = H1; a.outf = nullptr;
+    prof.mark(1, st);
     rc = tile == 256 ? launch_gemm<256, 256, 1>(a, R, st, err) : launch_gemm<128, 128, 1>(a, R, st, err);
+    prof.mark(1, st);
     if (rc) return rc;
     a.A = H1; a.Bt = W2t; a.N = H; a.Kdim = H; a.bias = b2; a.outb = H2;
+    prof.mark(2, st);
     rc = tile == 256 ? launch_gemm<256, 256, 2>(a, R, st, err) : launch_gemm<128, 128, 2>(a, R, st, err);
+    prof.mark(2, st);
     if (rc) return rc;
     a.A = H2; a.Bt = W3t; a.N = d; a.Kdim = H; a.bias = b3; a.outb = nullptr; a.outf = out;
+    prof.mark(3, st);
     rc = tile == 256 ? launch_gemm<256, 256, 3>(a, R, st, err) : launch_gemm<128, 128, 3>(a, R, st, err);
+    prof.mark(3, st);
     if (rc) return rc;
     SD_HIP_TRY(err, hipGetLastError());
     return SD_OK;

@@ -7,69 +7,101 @@ one batched call) -> ``sd_verify`` -> ``sd_advance``.  ``LangevinSampler`` loops
 """
 from __future__ import annotations
 
+from collections import defaultdict
+from contextlib import contextmanager
 from typing import Optional
 
 import torch
 
-from .binding import Context, Denoiser, SD_DRAFT_FROZEN
+from .binding import Context, Denoiser
+
+
+class StageTimer:
+    """HIP-event timing of chosen stages on the stream the kernels are launched on (torch's
+    current stream, whose handle the binding passes to the library)."""
+
+    def __init__(self, stages=None):
+        self.stages = None if stages is None else set(stages)
+        self._open = defaultdict(list)
+
+    @contextmanager
+    def stage(self, name: str, chains: int):
+        if self.stages is not None and name not in self.stages:
+            yield
+            return
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        yield
+        e1.record()
+        self._open[name].append((e0, e1, chains))
+
+    def collect(self):
+        """{stage: (total ms, launches, total chains)}; resets."""
+        torch.cuda.synchronize()
+        res = {}
+        for name, evs in self._open.items():
+            res[name] = (sum(a.elapsed_time(b) for a, b, _ in evs), len(evs), sum(c for _, _, c in evs))
+        self._open.clear()
+        return res
+
+
+class _NoTimer:
+    @contextmanager
+    def stage(self, name, chains):
+        yield
 
 
 class WindowBuffers:
     """Device buffers of one batch of at most B chains (layouts as in include/sd.h)."""
 
-    def __init__(self, B: int, d: int, K: int, out_rows: Optional[int] = None, device="cuda"):
+    def __init__(self, B: int, d: int, K: int, out_rows: Optional[int] = None, window: bool = True,
+                 device="cuda"):
         f32 = dict(dtype=torch.float32, device=device)
         self.B, self.d, self.K = B, d, K
         self.y = torch.zeros(B, d, **f32)
         self.n = torch.zeros(B, dtype=torch.int32, device=device)
         self.chain_id = torch.zeros(B, dtype=torch.int64, device=device)
-        self.D0 = torch.zeros(B, d, **f32)
-        self.Ytilde = torch.zeros(B, K, d, **f32)
-        self.krow = torch.full((B, K), -1, dtype=torch.int32, device=device)
-        self.Dq = torch.zeros(B, K, d, **f32)
+        if window:
+            self.D0 = torch.zeros(B, d, **f32)
+            self.Ytilde = torch.zeros(B, K, d, **f32)
+            self.krow = torch.full((B, K), -1, dtype=torch.int32, device=device)
+            self.Dq = torch.zeros(B, K, d, **f32)
         self.y_out = torch.zeros(B, d, **f32)
         self.adv = torch.zeros(B, dtype=torch.int32, device=device)
         self.rejected = torch.zeros(B, dtype=torch.uint8, device=device)
         self.out = torch.zeros(out_rows if out_rows is not None else B, d, **f32)
         self.B_active = torch.full((1,), B, dtype=torch.int32, device=device)
-        self.counters = torch.zeros(4, dtype=torch.int64, device=device)
+        self.counters = torch.zeros(5, dtype=torch.int64, device=device)
 
 
-class DiffusionSampler:
-    def __init__(self, ctx: Context, den: Denoiser, B: int, out_rows: Optional[int] = None):
-        self.ctx, self.den = ctx, den
-        self.buf = WindowBuffers(B, ctx.d, ctx.K, out_rows)
+class _SamplerBase:
+    timer = _NoTimer()
+
+    def _setup(self, ctx: Context, B: int, out_rows, window: bool):
+        self.ctx = ctx
+        self.buf = WindowBuffers(B, ctx.d, ctx.K, out_rows, window)
         self.ws = torch.empty(max(8, ctx.sd_workspace_bytes(B)), dtype=torch.uint8, device="cuda")
         ctx.sd_set_workspace(self.ws)
 
-    def start(self, chain_ids: torch.Tensor):
+    def start(self, chain_ids: torch.Tensor, reset_counters: bool = True) -> int:
         b = self.buf
         B = chain_ids.numel()
         b.chain_id[:B].copy_(chain_ids)
         self.ctx.sd_init_state(B, b.chain_id, b.y, b.n)
-        b.counters.zero_()
+        if reset_counters:
+            b.counters.zero_()
         return B
-
-    def window(self, B: int, diagnostics=None):
-        """One pass of the while-loop body for the first B chains of the buffers."""
-        b, ctx, den, d, K = self.buf, self.ctx, self.den, self.ctx.d, self.ctx.K
-        den.sdden_eval(B, b.y, b.n, b.D0)                       # D0 = D(y_n, n)
-        ctx.sd_draft(B, b.y, b.n, b.chain_id, b.D0, b.Ytilde, b.krow)
-        if K > 1:
-            # row (b,j) of Ytilde feeds row (b,j+1) of Dq: same flat layout shifted by one row;
-            # the last row of every chain is masked by krow, so the shifted write stays in bounds
-            den.sdden_eval(B * K, b.Ytilde.view(-1, d), b.krow.view(-1), b.Dq.view(-1, d)[1:])
-        lr, lu = diagnostics if diagnostics is not None else (None, None)
-        ctx.sd_verify(B, b.y, b.n, b.chain_id, b.D0, b.Dq, b.Ytilde, b.y_out, b.adv, b.rejected, lr, lu)
 
     def advance(self, B: int):
         b = self.buf
-        self.ctx.sd_advance(B, b.y_out, b.adv, b.rejected, b.y, b.n, b.chain_id, b.out, b.B_active, b.counters)
+        with self.timer.stage("advance", B):
+            self.ctx.sd_advance(B, b.y_out, b.adv, b.rejected, b.y, b.n, b.chain_id, b.out, b.B_active,
+                                b.counters)
 
-    def run(self, chain_ids: torch.Tensor):
+    def run(self, chain_ids: torch.Tensor, reset_counters: bool = True):
         """All chains to step T.  Returns (out tensor indexed by chain id, counters as a list
-        [sum adv, chain-windows, rejections, windows])."""
-        B = self.start(chain_ids)
+        [sum adv, chain-windows, rejections, windows, sum Kt])."""
+        B = self.start(chain_ids, reset_counters)
         while B > 0:
             self.window(B)
             self.advance(B)
@@ -77,36 +109,37 @@ class DiffusionSampler:
         return self.buf.out, self.buf.counters.tolist()
 
 
-class LangevinSampler:
+class DiffusionSampler(_SamplerBase):
+    def __init__(self, ctx: Context, den: Denoiser, B: int, out_rows: Optional[int] = None):
+        self.den = den
+        self._setup(ctx, B, out_rows, True)
+
+    def window(self, B: int, diagnostics=None):
+        """One pass of the while-loop body for the first B chains of the buffers."""
+        b, ctx, den, d, K, t = self.buf, self.ctx, self.den, self.ctx.d, self.ctx.K, self.timer
+        with t.stage("predict_start", B):
+            den.sdden_eval(B, b.y, b.n, b.D0)                   # D0 = D(y_n, n)
+        with t.stage("draft", B):
+            ctx.sd_draft(B, b.y, b.n, b.chain_id, b.D0, b.Ytilde, b.krow)
+        if K > 1:
+            # row (b,j) of Ytilde feeds row (b,j+1) of Dq: same flat layout shifted by one row;
+            # the last row of every chain is masked by krow, so the shifted write stays in bounds
+            with t.stage("predict_drafts", B):
+                den.sdden_eval(B * K, b.Ytilde.view(-1, d), b.krow.view(-1), b.Dq.view(-1, d)[1:])
+        lr, lu = diagnostics if diagnostics is not None else (None, None)
+        with t.stage("verify", B):
+            ctx.sd_verify(B, b.y, b.n, b.chain_id, b.D0, b.Dq, b.Ytilde, b.y_out, b.adv, b.rejected, lr, lu)
+
+
+class LangevinSampler(_SamplerBase):
     def __init__(self, ctx: Context, means: torch.Tensor, logw: torch.Tensor, comp_std: float,
                  gamma: float, B: int, out_rows: Optional[int] = None):
-        self.ctx, self.means, self.logw = ctx, means, logw
+        self.means, self.logw = means, logw
         self.comp_std, self.gamma, self.M = comp_std, gamma, means.shape[0]
-        self.buf = WindowBuffers(B, ctx.d, 1, out_rows)         # no draft / prediction buffers needed
-        self.ws = torch.empty(max(8, ctx.sd_workspace_bytes(B)), dtype=torch.uint8, device="cuda")
-        ctx.sd_set_workspace(self.ws)
-
-    def start(self, chain_ids: torch.Tensor):
-        b = self.buf
-        B = chain_ids.numel()
-        b.chain_id[:B].copy_(chain_ids)
-        self.ctx.sd_init_state(B, b.chain_id, b.y, b.n)
-        b.counters.zero_()
-        return B
+        self._setup(ctx, B, out_rows, False)
 
     def window(self, B: int, logratio=None, logu=None):
         b = self.buf
-        self.ctx.sd_langevin_window(B, b.y, b.n, b.chain_id, self.means, self.logw, self.comp_std, self.M,
-                                    self.gamma, b.y_out, b.adv, b.rejected, logratio, logu)
-
-    def advance(self, B: int):
-        b = self.buf
-        self.ctx.sd_advance(B, b.y_out, b.adv, b.rejected, b.y, b.n, b.chain_id, b.out, b.B_active, b.counters)
-
-    def run(self, chain_ids: torch.Tensor):
-        B = self.start(chain_ids)
-        while B > 0:
-            self.window(B)
-            self.advance(B)
-            B = int(self.buf.B_active.item())
-        return self.buf.out, self.buf.counters.tolist()
+        with self.timer.stage("langevin_window", B):
+            self.ctx.sd_langevin_window(B, b.y, b.n, b.chain_id, self.means, self.logw, self.comp_std,
+                                        self.M, self.gamma, b.y_out, b.adv, b.rejected, logratio, logu)

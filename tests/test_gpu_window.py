@@ -177,14 +177,14 @@ def test_advance_matches_oracle(B, d):
     gn, gid = dev(n, torch.int32), dev(ids, torch.int64)
     gout = torch.zeros(B, d, dtype=torch.float32, device="cuda")
     gB = torch.zeros(1, dtype=torch.int32, device="cuda")
-    cnt = torch.zeros(4, dtype=torch.int64, device="cuda")
+    cnt = torch.zeros(5, dtype=torch.int64, device="cuda")
     ctx.sd_advance(B, f32(y_out), dev(adv, torch.int32), dev(rej, torch.uint8), gy, gn, gid, gout, gB, cnt)
     Ba = int(host(gB)[0])
     assert Ba == n_ref.size
     assert np.array_equal(host(gn)[:Ba], n_ref) and np.array_equal(host(gid)[:Ba], id_ref)
     assert np.array_equal(host(gy)[:Ba], y_ref.astype(np.float32))
     assert np.array_equal(host(gout), out_ref.astype(np.float32))
-    assert host(cnt).tolist() == [int(adv.sum()), B, int(rej.sum()), 1]
+    assert host(cnt).tolist() == [int(adv.sum()), B, int(rej.sum()), 1, int(np.minimum(K, T - n).sum())]
 
 
 def test_gmm_denoiser_matches_oracle():
