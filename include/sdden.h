@@ -40,7 +40,7 @@ int sdden_lowrank_create(int32_t d, int32_t r, const float* mu, const float* U, 
  * host.  Time embedding of width E: emb[i] = sin(k w_i), emb[E/2+i] = cos(k w_i),
  * w_i = 10000^(-2i/E); its product with the last E rows of W1 is folded into a per-step bias
  * table at create time.  Rmax: rows reserved right away (as by sdden_reserve).
- * d and H must be multiples of 128. */
+ * d and H must be multiples of 256. */
 int sdden_mlp_create(int32_t d, int32_t H, int32_t E, const uint16_t* W1, const float* b1,
                      const uint16_t* W2, const float* b2, const uint16_t* W3, const float* b3,
                      int32_t T, int32_t Rmax, sdden** out);

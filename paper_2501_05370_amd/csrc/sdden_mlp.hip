@@ -22,158 +22,14 @@
 #include <new>
 #include <vector>
 
+#include "mlp_gemm.h"
 #include "sdden_internal.h"
 #include "sdden_rows.h"
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
+using mlpgemm::to_bf16_bits;
 constexpr int kThreads = 256;
-constexpr int BK = 64;
-constexpr int LDSK = BK + 8;      // padded LDS row, in bf16 elements
-
-struct MlpGemmArgs {
-  const uint16_t* A;     // [M, Kdim] bf16, dense
-  const uint16_t* Bt;    // [N, Kdim] bf16 (weights, transposed: row = output feature)
-  int N, Kdim;
-  const int32_t* count;  // device: M
-  const int32_t* rowidx; // dense row -> source row
-  const int32_t* krow;   // source row -> chain step
-  const float* bias;     // EPI 1: tb [T, N]; EPI 2, 3: b [N]
-  uint16_t* outb;        // EPI 1, 2: bf16 [M, N] dense
-  float* outf;           // EPI 3: fp32 [*, N] at source rows
-};
-
-__device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x)); }
-
-__device__ __forceinline__ uint16_t to_bf16_bits(float x) {
-  const __bf16 b = static_cast<__bf16>(x);
-  uint16_t u;
-  __builtin_memcpy(&u, &b, 2);
-  return u;
-}
-
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(kThreads) void mlp_gemm_kernel(MlpGemmArgs p) {
-  constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 MFMA tiles per wavefront, per dimension
-  constexpr int ACH = BM * (BK / 8) / kThreads;      // 16-byte chunks of A per thread per K-slice
-  constexpr int BCH = BN * (BK / 8) / kThreads;
-  extern __shared__ __align__(16) unsigned char smem[];
-  uint16_t* As = reinterpret_cast<uint16_t*>(smem);              // [2][BM][LDSK]
-  uint16_t* Bs = As + 2 * BM * LDSK;                             // [2][BN][LDSK]
-
-  const int M = *p.count;
-  const int tiles_n = p.N / BN;
-  // Tiles sharing a row panel of A are adjacent, 8 row panels form a group that sweeps N together.
-  constexpr int GROUP = 8;
-  const int tiles_m_all = gridDim.x / tiles_n;
-  const int per_group = GROUP * tiles_n;
-  const int group = blockIdx.x / per_group;
-  const int first_m = group * GROUP;
-  const int gsize = min(GROUP, tiles_m_all - first_m);
-  const int in_group = blockIdx.x % per_group;
-  const int tile_m = first_m + in_group % gsize;
-  const int tile_n = in_group / gsize;
-  if (tile_m * BM >= M) return;
-
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int half = lane >> 5, l32 = lane & 31;
-
-  const uint16_t* a_src[ACH];
-  const uint16_t* b_src[BCH];
-  int a_dst[ACH], b_dst[BCH];
-#pragma unroll
-  for (int i = 0; i < ACH; ++i) {
-    const int idx = t + kThreads * i;
-    const int row = idx >> 3, ch = idx & 7;
-    const int gm = min(tile_m * BM + row, M - 1);                // rows past M are loaded but never stored
-    a_src[i] = p.A + static_cast<int64_t>(gm) * p.Kdim + 8 * ch;
-    a_dst[i] = row * LDSK + 8 * ch;
-  }
-#pragma unroll
-  for (int i = 0; i < BCH; ++i) {
-    const int idx = t + kThreads * i;
-    const int row = idx >> 3, ch = idx & 7;
-    b_src[i] = p.Bt + static_cast<int64_t>(tile_n * BN + row) * p.Kdim + 8 * ch;
-    b_dst[i] = row * LDSK + 8 * ch;
-  }
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  uint4 ra[ACH], rb[BCH];
-  auto fetch = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < ACH; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_src[i] + k0);
-#pragma unroll
-    for (int i = 0; i < BCH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_src[i] + k0);
-  };
-  auto stash = [&](int s) {
-#pragma unroll
-    for (int i = 0; i < ACH; ++i) *reinterpret_cast<uint4*>(As + s * BM * LDSK + a_dst[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < BCH; ++i) *reinterpret_cast<uint4*>(Bs + s * BN * LDSK + b_dst[i]) = rb[i];
-  };
-
-  const int nk = p.Kdim / BK;
-  fetch(0);
-  stash(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int s = kt & 1;
-    if (kt + 1 < nk) fetch((kt + 1) * BK);
-    const uint16_t* Aw = As + s * BM * LDSK + (wm * (BM / 2) + l32) * LDSK + 8 * half;
-    const uint16_t* Bw = Bs + s * BN * LDSK + (wn * (BN / 2) + l32) * LDSK + 8 * half;
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 a[TM], b[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const uint4 u = *reinterpret_cast<const uint4*>(Aw + i * 32 * LDSK + kk);
-        __builtin_memcpy(&a[i], &u, 16);
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const uint4 u = *reinterpret_cast<const uint4*>(Bw + j * 32 * LDSK + kk);
-        __builtin_memcpy(&b[j], &u, 16);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) stash(s ^ 1);
-    __syncthreads();
-  }
-
-  // ---- epilogue: element (row = (v/4)*8 + half*4 + v%4, col = l32) of each 32x32 tile
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int gm = tile_m * BM + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-      if (gm >= M) continue;
-      const int src = p.rowidx[gm];
-      const float* brow = EPI == 1 ? p.bias + static_cast<int64_t>(p.krow[src]) * p.N : p.bias;
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int gn = tile_n * BN + wn * (BN / 2) + j * 32 + l32;
-        const float c = acc[i][j][v] + brow[gn];
-        if (EPI == 3) p.outf[static_cast<int64_t>(src) * p.N + gn] = c;
-        else p.outb[static_cast<int64_t>(gm) * p.N + gn] = to_bf16_bits(silu(c));
-      }
-    }
-  }
-}
 
 // X[rowidx[m], :] fp32 -> Xb[m, :] bf16, 8 elements per thread.
 __global__ __launch_bounds__(kThreads) void gather_convert_kernel(const float* __restrict__ X,
@@ -204,17 +60,12 @@ float bf16_bits_to_float(uint16_t b) {
   return f;
 }
 
-template <int BM, int BN, int EPI>
-int launch_gemm(const MlpGemmArgs& a, int Rmax, hipStream_t st, std::string& err) {
-  constexpr size_t shmem = 2 * static_cast<size_t>(BM + BN) * LDSK * sizeof(uint16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    SD_HIP_TRY(err, hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_gemm_kernel<BM, BN, EPI>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem)));
-    attr_set = true;
-  }
-  const int tiles_m = (Rmax + BM - 1) / BM, tiles_n = a.N / BN;
-  hipLaunchKernelGGL((mlp_gemm_kernel<BM, BN, EPI>), dim3(tiles_m * tiles_n), dim3(kThreads), shmem, st, a);
+// Large row counts: 256x256 tile, 8 wavefronts (4x2); small ones (the window-start call): 128x128,
+// 4 wavefronts, so that more workgroups are in flight.
+template <int EPI>
+int launch_gemm(const mlpgemm::Args& a, int R, hipStream_t st, std::string& err) {
+  hipError_t e = R > 1024 ? mlpgemm::launch<256, 256, 4, 2, EPI>(a, R, st) : mlpgemm::launch<128, 128, 2, 2, EPI>(a, R, st);
+  if (e != hipSuccess) return sdi::fail(err, SD_ERR_HIP, "mlp gemm launch: %s", hipGetErrorString(e));
   return SD_OK;
 }
 
@@ -225,7 +76,6 @@ struct MlpDenoiser final : sdden {
   int32_t *rowidx = nullptr, *count = nullptr;
   uint16_t *Xb = nullptr, *H1 = nullptr, *H2 = nullptr;
   int cap_rows = 0;
-  int tile = 128;                                             // workgroup tile edge (128 or 256)
 
   ~MlpDenoiser() override {
     for (void* q : {static_cast<void*>(W1t), static_cast<void*>(W2t), static_cast<void*>(W3t), static_cast<void*>(tb),
@@ -239,10 +89,15 @@ struct MlpDenoiser final : sdden {
     for (void* q : {static_cast<void*>(rowidx), static_cast<void*>(Xb), static_cast<void*>(H1), static_cast<void*>(H2)})
       if (q) (void)hipFree(q);
     rowidx = nullptr; Xb = H1 = H2 = nullptr; cap_rows = 0;
-    SD_HIP_TRY(err, hipMalloc(&rowidx, sizeof(int32_t) * static_cast<size_t>(R)));
-    SD_HIP_TRY(err, hipMalloc(&Xb, 2 * static_cast<size_t>(R) * d));
-    SD_HIP_TRY(err, hipMalloc(&H1, 2 * static_cast<size_t>(R) * H));
-    SD_HIP_TRY(err, hipMalloc(&H2, 2 * static_cast<size_t>(R) * H));
+    // the GEMM reads whole tiles of its A operand: round the row capacity up
+    const size_t Rp = (static_cast<size_t>(R) + mlpgemm::kRowPad - 1) / mlpgemm::kRowPad * mlpgemm::kRowPad;
+    SD_HIP_TRY(err, hipMalloc(&rowidx, sizeof(int32_t) * Rp));
+    SD_HIP_TRY(err, hipMalloc(&Xb, 2 * Rp * d));
+    SD_HIP_TRY(err, hipMalloc(&H1, 2 * Rp * H));
+    SD_HIP_TRY(err, hipMalloc(&H2, 2 * Rp * H));
+    SD_HIP_TRY(err, hipMemset(Xb, 0, 2 * Rp * d));
+    SD_HIP_TRY(err, hipMemset(H1, 0, 2 * Rp * H));
+    SD_HIP_TRY(err, hipMemset(H2, 0, 2 * Rp * H));
     if (!count) SD_HIP_TRY(err, hipMalloc(&count, sizeof(int32_t)));
     cap_rows = R;
     return SD_OK;
@@ -257,22 +112,22 @@ struct MlpDenoiser final : sdden {
     const int64_t chunks = static_cast<int64_t>(R) * (d / 8);
     const int cgrid = static_cast<int>(std::min<int64_t>((chunks + kThreads - 1) / kThreads, 256 * 32));
     hipLaunchKernelGGL(gather_convert_kernel, dim3(cgrid), dim3(kThreads), 0, st, X, rowidx, count, Xb, d);
-    MlpGemmArgs a;
+    mlpgemm::Args a;
     a.count = count; a.rowidx = rowidx; a.krow = krow;
     int rc;
     a.A = Xb; a.Bt = W1t; a.N = H; a.Kdim = d; a.bias = tb; a.outb = H1; a.outf = nullptr;
     prof.mark(1, st);
-    rc = tile == 256 ? launch_gemm<256, 256, 1>(a, R, st, err) : launch_gemm<128, 128, 1>(a, R, st, err);
+    rc = launch_gemm<1>(a, R, st, err);
     prof.mark(1, st);
     if (rc) return rc;
     a.A = H1; a.Bt = W2t; a.N = H; a.Kdim = H; a.bias = b2; a.outb = H2;
     prof.mark(2, st);
-    rc = tile == 256 ? launch_gemm<256, 256, 2>(a, R, st, err) : launch_gemm<128, 128, 2>(a, R, st, err);
+    rc = launch_gemm<2>(a, R, st, err);
     prof.mark(2, st);
     if (rc) return rc;
     a.A = H2; a.Bt = W3t; a.N = d; a.Kdim = H; a.bias = b3; a.outb = nullptr; a.outf = out;
     prof.mark(3, st);
-    rc = tile == 256 ? launch_gemm<256, 256, 3>(a, R, st, err) : launch_gemm<128, 128, 3>(a, R, st, err);
+    rc = launch_gemm<3>(a, R, st, err);
     prof.mark(3, st);
     if (rc) return rc;
     SD_HIP_TRY(err, hipGetLastError());
@@ -299,16 +154,11 @@ extern "C" int sdden_mlp_create(int32_t d, int32_t H, int32_t E, const uint16_t*
   std::string& ER = sdi::g_den_create_error;
   if (!W1 || !b1 || !W2 || !b2 || !W3 || !b3 || !out || d <= 0 || H <= 0 || E < 0 || (E & 1) || T <= 0 || Rmax <= 0)
     return sdi::fail(ER, SD_ERR_ARG, "sdden_mlp_create: bad argument");
-  if (d % 128 != 0 || H % 128 != 0)
-    return sdi::fail(ER, SD_ERR_UNSUPPORTED, "sdden_mlp_create: d=%d and H=%d must be multiples of 128", d, H);
+  if (d % 256 != 0 || H % 256 != 0)
+    return sdi::fail(ER, SD_ERR_UNSUPPORTED, "sdden_mlp_create: d=%d and H=%d must be multiples of 256", d, H);
   MlpDenoiser* m = new (std::nothrow) MlpDenoiser;
   if (!m) return sdi::fail(ER, SD_ERR_ARG, "sdden_mlp_create: out of host memory");
   m->d = d; m->T = T; m->H = H; m->E = E;
-  m->tile = (d % 256 == 0 && H % 256 == 0) ? 256 : 128;
-  if (const char* env = std::getenv("SDDEN_MLP_TILE")) {
-    const int v = std::atoi(env);
-    if (v == 128 || (v == 256 && m->tile == 256)) m->tile = v;
-  }
   // per-step bias table: tb[k] = b1 + emb(k) . W1[d:d+E, :],  emb = [sin(k w_i) ; cos(k w_i)], w_i = 10000^(-2i/E)
   std::vector<float> tb(static_cast<size_t>(T) * H);
   {

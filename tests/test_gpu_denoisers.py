@@ -47,7 +47,7 @@ def test_lowrank_denoiser_matches_oracle(d, r, T, R):
     assert np.all(host(out)[:5] == got[:5])
 
 
-@pytest.mark.parametrize("d,H,E,T,R", [(128, 128, 8, 20, 300), (256, 512, 16, 40, 700), (384, 256, 256, 30, 150)])
+@pytest.mark.parametrize("d,H,E,T,R", [(256, 256, 8, 20, 300), (256, 512, 16, 40, 2000), (768, 256, 256, 30, 1100)])
 def test_mlp_denoiser_matches_oracle(d, H, E, T, R):
     from paper_2501_05370_amd.binding import Denoiser
     rng = np.random.default_rng(1)
