@@ -50,7 +50,7 @@ constexpr size_t lds_bytes() {
 
 // EPI 1: out = bf16(silu(acc + bias[krow[src]][n]));  EPI 2: out = bf16(silu(acc + bias[n]));
 // EPI 3: outf[src][n] = acc + bias[n].
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, int PM = 4, int PN = 8>
 __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   constexpr int NT = 64 * WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;       // MFMA tiles per wavefront
@@ -65,17 +65,19 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
 
   const int M = *p.count;
   const int tiles_n = p.N / BN;
-  // 8 row panels form a group that sweeps N together: tiles that run at the same time share
-  // their A rows and walk the same columns of the weights.
-  constexpr int GROUP = 8;
-  const int tiles_m_all = gridDim.x / tiles_n;
-  const int per_group = GROUP * tiles_n;
-  const int group = blockIdx.x / per_group;
-  const int first_m = group * GROUP;
-  const int gsize = min(GROUP, tiles_m_all - first_m);
-  const int in_group = blockIdx.x % per_group;
-  const int tile_m = first_m + in_group % gsize;
-  const int tile_n = in_group / gsize;
+  // Workgroups are handed to the 8 XCDs round-robin (id % 8), and each XCD has its own L2.  Give
+  // every XCD a contiguous run of tiles, ordered as PM x PN patches, so that the ~32 tiles an XCD
+  // works on at a time share PM row panels of A and PN row panels of the weights.
+  int tile_m, tile_n;
+  {
+    const int per_xcd = gridDim.x / 8;                           // host launches a multiple of 8
+    const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int patches_n = (tiles_n + PN - 1) / PN;
+    const int patch = L / (PM * PN), within = L % (PM * PN);
+    tile_m = (patch / patches_n) * PM + within % PM;
+    tile_n = (patch % patches_n) * PN + within / PM;
+    if (tile_n >= tiles_n) return;
+  }
   if (tile_m * BM >= M) return;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -84,8 +86,13 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   const int Kd = p.Kdim;
 
   // this thread's 16-byte chunk: tile row t/8 (+ ROWS_PER_PASS per pass), K offset 8*(t%8)
+#ifdef MLPGEMM_EXPERIMENT_SAME_PANEL   /* measurement experiment only: every tile reads panel 0 */
+  const uint16_t* a_thr = p.A + (static_cast<size_t>(0) * BM + (t >> 3)) * Kd + 8 * (t & 7);
+  const uint16_t* b_thr = p.Bt + (static_cast<size_t>(0) * BN + (t >> 3)) * Kd + 8 * (t & 7);
+#else
   const uint16_t* a_thr = p.A + (static_cast<size_t>(tile_m) * BM + (t >> 3)) * Kd + 8 * (t & 7);
   const uint16_t* b_thr = p.Bt + (static_cast<size_t>(tile_n) * BN + (t >> 3)) * Kd + 8 * (t & 7);
+#endif
   const int lds_thr = (t >> 3) * LDSK + 8 * (t & 7);
 
   f32x16 acc[TM][TN];
@@ -163,18 +170,20 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
 }
 
 // Enqueue the GEMM for up to Rmax rows (the kernel reads the true M on the device).
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, int PM = 4, int PN = 8>
 hipError_t launch(const Args& a, int Rmax, hipStream_t st) {
   constexpr size_t shmem = lds_bytes<BM, BN, WM, WN>();
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, EPI>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, EPI, PM, PN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int tiles_m = (Rmax + BM - 1) / BM, tiles_n = a.N / BN;
-  hipLaunchKernelGGL((kernel<BM, BN, WM, WN, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WM * WN), shmem, st, a);
+  const int patches = ((tiles_m + PM - 1) / PM) * ((tiles_n + PN - 1) / PN);
+  const int grid = (patches * PM * PN + 7) / 8 * 8;
+  hipLaunchKernelGGL((kernel<BM, BN, WM, WN, EPI, PM, PN>), dim3(grid), dim3(64 * WM * WN), shmem, st, a);
   return hipGetLastError();
 }
 
