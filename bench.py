@@ -51,7 +51,7 @@ def roofline_plan(cfg):
     d, K = cfg.d, cfg.K
     if cfg.kind == "mlp":
         H = cfg.params.H
-        return dict(kernel="mlpgemm::kernel<256,256,4,2,1> (layer 1: rows x 12288 -> 4096, bf16 MFMA)", den_which=1,
+        return dict(kernel="mlpgemm::kernel<256,256,2,4,1> (layer 1: rows x 12288 -> 4096, bf16 MFMA)", den_which=1,
                     bound="mfma", peak="mfma_bf16", scale=1e-12,
                     work=lambda c: 2.0 * c[4] * d * H)                 # rows evaluated = sum Kt
     if cfg.kind == "lowrank":

@@ -2,11 +2,16 @@
 // MLP denoiser:  C[M,N] = A[M,K] * Bt[N,K]^T, both operands K-contiguous.
 //
 // Workgroup tile BM x BN x 64, WM x WN wavefronts, each wavefront owns (BM/WM) x (BN/WN) of the
-// tile as 32x32 v_mfma_f32_32x32x16_bf16 accumulators.  The K-slice of both operands is staged in
-// LDS (rows padded to 72 elements: the 16-byte fragment reads of any 8 consecutive lanes then cover
-// all 32 banks); the next slice is fetched into registers while the current one feeds the MFMAs.
-// A must be readable for all rows of every launched tile (callers round their row capacity up to a
-// multiple of BM); rows >= M are computed on whatever is there and never stored.
+// tile as 32x32 v_mfma_f32_32x32x16_bf16 accumulators.  K-slices go from global memory straight
+// into LDS (global_load_lds_dwordx4): no staging registers and no LDS store instructions.  One
+// wavefront load fills 1 KiB of LDS = 8 rows of a 64-element slice, lane l landing at byte 16*l;
+// bank conflicts are avoided by permuting which 16-byte chunk of its row a lane fetches
+// (chunk ^ row%8) instead of padding rows, so the 16-byte fragment reads of any 8 consecutive
+// rows cover all 32 banks.  Two LDS stages: the next slice streams in while the current one feeds
+// the MFMAs.  Tiles are ordered in PM x PN patches per XCD (workgroups go to the 8 XCDs
+// round-robin and each XCD has its own L2).
+// A must be readable for all rows of every launched tile (callers round their row capacity up to
+// kRowPad); rows >= M are computed on whatever is there and never stored.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -19,7 +24,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;
-constexpr int LDSK = BK + 8;      // padded LDS row, in bf16 elements
 constexpr int kRowPad = 256;      // row capacity of A operands must be a multiple of this
 
 struct Args {
@@ -43,34 +47,23 @@ __device__ __forceinline__ uint16_t to_bf16_bits(float x) {
   return u;
 }
 
-template <int BM, int BN, int WM, int WN>
-constexpr size_t lds_bytes() {
-  return 2 * static_cast<size_t>(BM + BN) * LDSK * sizeof(uint16_t);
-}
-
 // EPI 1: out = bf16(silu(acc + bias[krow[src]][n]));  EPI 2: out = bf16(silu(acc + bias[n]));
 // EPI 3: outf[src][n] = acc + bias[n].
 template <int BM, int BN, int WM, int WN, int EPI, int PM = 4, int PN = 8>
 __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
-  constexpr int NT = 64 * WM * WN;
-  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;       // MFMA tiles per wavefront
-  constexpr int ACH = BM * (BK / 8) / NT;                    // 16-byte chunks per thread per K-slice
-  constexpr int BCH = BN * (BK / 8) / NT;
-  constexpr int ROWS_PER_PASS = NT / 8;                      // tile rows covered by one chunk pass
-  static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wavefront tile must be whole MFMA tiles");
-  static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "chunks must divide evenly");
-  extern __shared__ __align__(16) unsigned char smem[];
-  uint16_t* As = reinterpret_cast<uint16_t*>(smem);          // [2][BM][LDSK]
-  uint16_t* Bs = As + 2 * BM * LDSK;                         // [2][BN][LDSK]
+  constexpr int NW = WM * WN;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int APASS = BM / 8 / NW, BPASS = BN / 8 / NW;    // wavefront loads per K-slice
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "row groups must divide evenly");
+  extern __shared__ __align__(1024) unsigned char smem[];
+  unsigned char* As = smem;                                  // [2][BM][128 B]
+  unsigned char* Bs = smem + 2 * BM * 128;                   // [2][BN][128 B]
 
   const int M = *p.count;
   const int tiles_n = p.N / BN;
-  // Workgroups are handed to the 8 XCDs round-robin (id % 8), and each XCD has its own L2.  Give
-  // every XCD a contiguous run of tiles, ordered as PM x PN patches, so that the ~32 tiles an XCD
-  // works on at a time share PM row panels of A and PN row panels of the weights.
   int tile_m, tile_n;
   {
-    const int per_xcd = gridDim.x / 8;                           // host launches a multiple of 8
+    const int per_xcd = gridDim.x / 8;
     const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     const int patches_n = (tiles_n + PN - 1) / PN;
     const int patch = L / (PM * PN), within = L % (PM * PN);
@@ -85,15 +78,13 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   const int half = lane >> 5, l32 = lane & 31;
   const int Kd = p.Kdim;
 
-  // this thread's 16-byte chunk: tile row t/8 (+ ROWS_PER_PASS per pass), K offset 8*(t%8)
-#ifdef MLPGEMM_EXPERIMENT_SAME_PANEL   /* measurement experiment only: every tile reads panel 0 */
-  const uint16_t* a_thr = p.A + (static_cast<size_t>(0) * BM + (t >> 3)) * Kd + 8 * (t & 7);
-  const uint16_t* b_thr = p.Bt + (static_cast<size_t>(0) * BN + (t >> 3)) * Kd + 8 * (t & 7);
-#else
-  const uint16_t* a_thr = p.A + (static_cast<size_t>(tile_m) * BM + (t >> 3)) * Kd + 8 * (t & 7);
-  const uint16_t* b_thr = p.Bt + (static_cast<size_t>(tile_n) * BN + (t >> 3)) * Kd + 8 * (t & 7);
-#endif
-  const int lds_thr = (t >> 3) * LDSK + 8 * (t & 7);
+  // lane's source: row (8*group + lane/8), 16-byte chunk (lane%8) ^ (lane/8)
+  const int lrow = lane >> 3, lchunk = (lane & 7) ^ (lane >> 3);
+  const unsigned char* a_lane = reinterpret_cast<const unsigned char*>(p.A) +
+                                (static_cast<size_t>(tile_m) * BM + 8 * wave + lrow) * Kd * 2 + 16 * lchunk;
+  const unsigned char* b_lane = reinterpret_cast<const unsigned char*>(p.Bt) +
+                                (static_cast<size_t>(tile_n) * BN + 8 * wave + lrow) * Kd * 2 + 16 * lchunk;
+  const size_t pass_stride = static_cast<size_t>(8 * NW) * Kd * 2;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -103,53 +94,51 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  u32x4 ra[ACH], rb[BCH];
-#define MLPGEMM_FETCH(k0)                                                                              \
+  typedef __attribute__((address_space(3))) void* lds_ptr;
+  typedef const __attribute__((address_space(1))) void* gbl_ptr;
+#define MLPGEMM_FETCH(s_, k0)                                                                        \
   do {                                                                                                 \
-    _Pragma("unroll") for (int i_ = 0; i_ < ACH; ++i_)                                                 \
-        ra[i_] = *reinterpret_cast<const u32x4*>(a_thr + static_cast<size_t>(i_) * ROWS_PER_PASS * Kd + (k0)); \
-    _Pragma("unroll") for (int i_ = 0; i_ < BCH; ++i_)                                                 \
-        rb[i_] = *reinterpret_cast<const u32x4*>(b_thr + static_cast<size_t>(i_) * ROWS_PER_PASS * Kd + (k0)); \
-  } while (0)
-#define MLPGEMM_STASH(s_)                                                                              \
-  do {                                                                                                 \
-    _Pragma("unroll") for (int i_ = 0; i_ < ACH; ++i_)                                                 \
-        *reinterpret_cast<u32x4*>(As + (s_) * BM * LDSK + lds_thr + i_ * ROWS_PER_PASS * LDSK) = ra[i_]; \
-    _Pragma("unroll") for (int i_ = 0; i_ < BCH; ++i_)                                                 \
-        *reinterpret_cast<u32x4*>(Bs + (s_) * BN * LDSK + lds_thr + i_ * ROWS_PER_PASS * LDSK) = rb[i_]; \
+    _Pragma("unroll") for (int i_ = 0; i_ < APASS; ++i_)                                               \
+        __builtin_amdgcn_global_load_lds((gbl_ptr)(a_lane + i_ * pass_stride + (k0) * 2),              \
+                                         (lds_ptr)(As + (s_) * BM * 128 + (i_ * NW + wave) * 1024), 16, 0, 0); \
+    _Pragma("unroll") for (int i_ = 0; i_ < BPASS; ++i_)                                               \
+        __builtin_amdgcn_global_load_lds((gbl_ptr)(b_lane + i_ * pass_stride + (k0) * 2),              \
+                                         (lds_ptr)(Bs + (s_) * BN * 128 + (i_ * NW + wave) * 1024), 16, 0, 0); \
   } while (0)
 
   const int nk = Kd / BK;
-  MLPGEMM_FETCH(0);
-  MLPGEMM_STASH(0);
+  MLPGEMM_FETCH(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  // fragment addressing: row r, chunk c -> r*128 + ((c ^ (r & 7)) << 4); r & 7 == l32 & 7 for all tiles
+  const int a_row = (wm * (BM / WM) + l32) * 128, b_row = (wn * (BN / WN) + l32) * 128;
+  const int sw = l32 & 7;
   for (int kt = 0; kt < nk; ++kt) {
     const int s = kt & 1;
-    if (kt + 1 < nk) MLPGEMM_FETCH((kt + 1) * BK);
-    const uint16_t* Aw = As + s * BM * LDSK + (wm * (BM / WM) + l32) * LDSK + 8 * half;
-    const uint16_t* Bw = Bs + s * BN * LDSK + (wn * (BN / WN) + l32) * LDSK + 8 * half;
+    if (kt + 1 < nk) MLPGEMM_FETCH(s ^ 1, (kt + 1) * BK);
+    const unsigned char* Aw = As + s * BM * 128 + a_row;
+    const unsigned char* Bw = Bs + s * BN * 128 + b_row;
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
+    for (int kk = 0; kk < 4; ++kk) {
+      const int off = ((2 * kk + half) ^ sw) << 4;
       bf16x8 a[TM], b[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Aw + i * 32 * LDSK + kk));
+        a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Aw + i * 32 * 128 + off));
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bw + j * 32 * LDSK + kk));
+        b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bw + j * 32 * 128 + off));
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) MLPGEMM_STASH(s ^ 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
 #undef MLPGEMM_FETCH
-#undef MLPGEMM_STASH
 
-  // ---- epilogue: element (row = (v/4)*8 + half*4 + v%4, col = l32) of each 32x32 tile
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -169,10 +158,9 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   }
 }
 
-// Enqueue the GEMM for up to Rmax rows (the kernel reads the true M on the device).
 template <int BM, int BN, int WM, int WN, int EPI, int PM = 4, int PN = 8>
 hipError_t launch(const Args& a, int Rmax, hipStream_t st) {
-  constexpr size_t shmem = lds_bytes<BM, BN, WM, WN>();
+  constexpr size_t shmem = 2 * static_cast<size_t>(BM + BN) * 128;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, EPI, PM, PN>),

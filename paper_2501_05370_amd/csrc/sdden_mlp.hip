@@ -60,11 +60,11 @@ float bf16_bits_to_float(uint16_t b) {
   return f;
 }
 
-// Large row counts: 256x256 tile, 8 wavefronts (4x2); small ones (the window-start call): 128x128,
+// Large row counts: 256x256 tile, 8 wavefronts (2x4); small ones (the window-start call): 128x128,
 // 4 wavefronts, so that more workgroups are in flight.
 template <int EPI>
 int launch_gemm(const mlpgemm::Args& a, int R, hipStream_t st, std::string& err) {
-  hipError_t e = R > 1024 ? mlpgemm::launch<256, 256, 4, 2, EPI>(a, R, st) : mlpgemm::launch<128, 128, 2, 2, EPI>(a, R, st);
+  hipError_t e = R > 1024 ? mlpgemm::launch<256, 256, 2, 4, EPI>(a, R, st) : mlpgemm::launch<128, 128, 2, 2, EPI>(a, R, st);
   if (e != hipSuccess) return sdi::fail(err, SD_ERR_HIP, "mlp gemm launch: %s", hipGetErrorString(e));
   return SD_OK;
 }
