@@ -14,7 +14,7 @@
 namespace {
 
 constexpr int kBlock = 256;   // threads per workgroup (4 wavefronts of 64)
-constexpr int kJC = 16;       // window positions reduced together in the verify kernel
+constexpr int kJC = 8;        // window positions reduced together in the verify kernel
 
 std::string g_create_error;
 
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
   __shared__ int sh_jr[CPW];
   __shared__ double sh_coef[CPW];
 
-  const int slot = threadIdx.x / TPC;
+  const int slot = TPC == kBlock ? 0 : threadIdx.x / TPC;     // whole workgroup on one chain: uniform
   const int t = threadIdx.x % TPC;
   const int b_raw = blockIdx.x * CPW + slot;
   const int Bact = active_chains(p.active, p.B);
