@@ -51,7 +51,7 @@ def roofline_plan(cfg):
     d, K = cfg.d, cfg.K
     if cfg.kind == "mlp":
         H = cfg.params.H
-        return dict(kernel="mlpgemm::kernel<256,256,2,4,1> (layer 1: rows x 12288 -> 4096, bf16 MFMA)", den_which=1,
+        return dict(kernel="mlpgemm::kernel<..., EPI=1> layer-1 GEMM rows x 12288 -> 4096, bf16 MFMA (256x256 tile for the batched call, 128x128 for the window-start call)", den_which=1,
                     bound="mfma", peak="mfma_bf16", scale=1e-12,
                     work=lambda c: 2.0 * c[4] * d * H)                 # rows evaluated = sum Kt
     if cfg.kind == "lowrank":
@@ -178,7 +178,18 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(DESCRIPTIONS))
     ap.add_argument("--stages", action="store_true", help="time every stage (adds event overhead)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy (reference for scaling rocprof FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 5}))
+        return
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (chains are independent and would shard by "
                          "chain id with no collective on the hot path); run with --gpus 1")
