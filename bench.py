@@ -56,7 +56,7 @@ def roofline_plan(cfg):
                     work=lambda c: 2.0 * c[4] * d * H)                 # rows evaluated = sum Kt
     if cfg.kind == "lowrank":
         rpad = -(-cfg.params.U.shape[1] // 16) * 16
-        return dict(kernel="lowrank_gemm_kernel<2> (P' Q^T + epilogue, fp32 MFMA)", den_which=2,
+        return dict(kernel="lowrank_gemm_kernel<2,128> (P' Q^T + epilogue, fp32 MFMA)", den_which=2,
                     bound="mfma", peak="mfma_fp32", scale=1e-12,
                     work=lambda c: 2.0 * c[4] * d * rpad)
     if cfg.kind == "gmm":
@@ -68,7 +68,7 @@ def roofline_plan(cfg):
     if cfg.kind == "langevin":
         M = cfg.params.means.shape[0]
         # fp64 flops per evaluated position: logits 3 M d, gradient 2 M d + 2 d, Delta / dots / update 12 d
-        return dict(kernel="langevin_window_kernel (fused draft + score + verify)", stage="langevin_window",
+        return dict(kernel="langevin_window_wave_kernel<4> (fused draft + score + verify, one wavefront per chain)", stage="langevin_window",
                     bound="alu", peak="alu_fp64", scale=1e-12,
                     work=lambda c: float(c[0] + c[1]) * d * (5.0 * M + 14.0))
     raise ValueError(cfg.kind)

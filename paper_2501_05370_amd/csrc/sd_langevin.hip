@@ -213,6 +213,260 @@ __global__ __launch_bounds__(kThreads) void langevin_window_kernel(LangevinArgs 
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// One WAVEFRONT per chain (d <= 1024 * CPT/4): no workgroup barrier on the walk at all.
+// A lane owns CPT groups of four coordinates; the mixture means sit in LDS once per workgroup
+// (kWaveChains chains share them).  Logits use  log w_m + (x.mu_m - |mu_m|^2/2)/s^2  (the |x|^2 term
+// cancels in the softmax), so a position costs two passes over the means: 16 dot products and the
+// responsibility-weighted mean.  The 16 per-lane partial dot products are reduced with a transposed
+// butterfly (values are exchanged in halves, 17 shuffles instead of 96); responsibilities are then
+// broadcast through scalar registers.
+// ---------------------------------------------------------------------------------------------
+constexpr int kWaveChains = 4;             // chains (wavefronts) per workgroup
+constexpr int kWaveM = 16;                 // components handled by the transposed reduction
+
+__device__ __forceinline__ double dpp_xor(double v, int mask) { return __shfl_xor(v, mask, 64); }
+
+// in: 16 per-lane partial sums; out: total of value ((lane >> 2) & 15), on every lane
+__device__ __forceinline__ double reduce16_transposed(double (&a)[16], int lane) {
+  {
+    const bool up = lane & 32;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const double send = up ? a[i] : a[i + 8];
+      const double keep = up ? a[i + 8] : a[i];
+      a[i] = keep + dpp_xor(send, 32);
+    }
+  }
+  {
+    const bool up = lane & 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double send = up ? a[i] : a[i + 4];
+      const double keep = up ? a[i + 4] : a[i];
+      a[i] = keep + dpp_xor(send, 16);
+    }
+  }
+  {
+    const bool up = lane & 8;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const double send = up ? a[i] : a[i + 2];
+      const double keep = up ? a[i + 2] : a[i];
+      a[i] = keep + dpp_xor(send, 8);
+    }
+  }
+  {
+    const bool up = lane & 4;
+    const double send = up ? a[0] : a[1];
+    const double keep = up ? a[1] : a[0];
+    a[0] = keep + dpp_xor(send, 4);
+  }
+  a[0] += dpp_xor(a[0], 2);
+  a[0] += dpp_xor(a[0], 1);
+  return a[0];
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int src_lane) {
+  const long long bits = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_readlane(static_cast<int>(bits), src_lane);
+  const int hi = __builtin_amdgcn_readlane(static_cast<int>(bits >> 32), src_lane);
+  return __longlong_as_double((static_cast<long long>(hi) << 32) | static_cast<unsigned int>(lo));
+}
+
+template <int CPT>
+__global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kernel(LangevinArgs p, int dpad) {
+  extern __shared__ __align__(16) float sh_mu[];          // [kWaveM][dpad], rows beyond M and the pad are 0
+  __shared__ double sh_hn[kWaveM];                         // |mu_m|^2 / 2
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int d = p.d, M = p.M;
+
+  for (int idx = t; idx < kWaveM * dpad; idx += 64 * kWaveChains) {
+    const int m = idx / dpad, i = idx % dpad;
+    sh_mu[idx] = (m < M && i < d) ? p.means[static_cast<int64_t>(m) * d + i] : 0.f;
+  }
+  __syncthreads();
+  if (wave == 0) {                                         // half squared norms, fp64
+    double part[16];
+#pragma unroll
+    for (int m = 0; m < kWaveM; ++m) {
+      double acc = 0.0;
+      for (int i = lane; i < dpad; i += 64) {
+        const double v = sh_mu[m * dpad + i];
+        acc = fma(v, v, acc);
+      }
+      part[m] = acc;
+    }
+    const double tot = reduce16_transposed(part, lane);
+    if ((lane & 3) == 0) sh_hn[lane >> 2] = 0.5 * tot;
+  }
+  __syncthreads();                                         // last workgroup-wide barrier
+
+  const int Bact = p.active ? min(p.B, max(0, *p.active)) : p.B;
+  const int b = blockIdx.x * kWaveChains + wave;
+  if (b >= Bact) return;                                   // whole wavefront leaves
+  const int n = p.n[b];
+  const int Kt = max(0, min(p.K, p.T - n));
+  const int64_t id = p.id[b];
+  const double gamma = p.gamma, inv_s2 = p.inv_s2;
+  const double sq2g = sqrt(2.0 * gamma), sqg2 = sqrt(0.5 * gamma);
+  const int my_m = lane >> 2;                              // component this lane holds after a reduction
+  const double my_logw = my_m < M ? static_cast<double>(p.logw[my_m]) : 0.0;
+  const double my_hn = sh_hn[my_m];
+
+  bool own[CPT][4];
+  double cur[CPT][4];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int i0 = 4 * (lane + 64 * c);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      own[c][e] = i0 + e < d;
+      cur[c][e] = own[c][e] ? static_cast<double>(p.x[static_cast<int64_t>(b) * d + i0 + e]) : 0.0;
+    }
+  }
+
+  // grad E at `cur` for my coordinates
+  auto gradient = [&](double g[CPT][4]) {
+    double dot[16];
+#pragma unroll
+    for (int m = 0; m < kWaveM; ++m) dot[m] = 0.0;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {                        // 16 independent accumulation chains
+      const int g4 = lane + 64 * c;
+      if (4 * g4 < dpad) {
+#pragma unroll
+        for (int m = 0; m < kWaveM; ++m) {
+          const float4 mu = *reinterpret_cast<const float4*>(&sh_mu[m * dpad + 4 * g4]);
+          dot[m] = fma(cur[c][0], static_cast<double>(mu.x), dot[m]);
+          dot[m] = fma(cur[c][1], static_cast<double>(mu.y), dot[m]);
+          dot[m] = fma(cur[c][2], static_cast<double>(mu.z), dot[m]);
+          dot[m] = fma(cur[c][3], static_cast<double>(mu.w), dot[m]);
+        }
+      }
+    }
+    const double tot = reduce16_transposed(dot, lane);     // x . mu_{my_m}
+    double logit = my_m < M ? my_logw + (tot - my_hn) * inv_s2 : -INFINITY;
+    double mx = logit;
+#pragma unroll
+    for (int s = 4; s <= 32; s <<= 1) mx = fmax(mx, dpp_xor(mx, s));
+    const double ex = my_m < M ? exp(logit - mx) : 0.0;
+    double sum = ex;
+#pragma unroll
+    for (int s = 4; s <= 32; s <<= 1) sum += dpp_xor(sum, s);
+    const double r_mine = ex / sum;
+    double bar[CPT][4];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bar[c][e] = 0.0;
+#pragma unroll
+    for (int m = 0; m < kWaveM; ++m) {
+      const double r = readlane_f64(r_mine, 4 * m);        // uniform: lives in scalar registers
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int g4 = lane + 64 * c;
+        if (4 * g4 < dpad) {
+          const float4 mu = *reinterpret_cast<const float4*>(&sh_mu[m * dpad + 4 * g4]);
+          bar[c][0] = fma(r, static_cast<double>(mu.x), bar[c][0]);
+          bar[c][1] = fma(r, static_cast<double>(mu.y), bar[c][1]);
+          bar[c][2] = fma(r, static_cast<double>(mu.z), bar[c][2]);
+          bar[c][3] = fma(r, static_cast<double>(mu.w), bar[c][3]);
+        }
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < CPT; ++c)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) g[c][e] = (cur[c][e] - bar[c][e]) * inv_s2;
+  };
+
+  double g0[CPT][4];
+  gradient(g0);
+
+  int jr = -1;
+  double coef = 0.0;
+  double dl[CPT][4];                                       // gradient at the draft, then Delta
+  float z[CPT][4];
+  for (int j = 0; j < Kt; ++j) {                           // Kt is uniform over the wavefront
+    const uint32_t k1 = static_cast<uint32_t>(n + j + 1);
+#pragma unroll
+    for (int c = 0; c < CPT; ++c)
+      sdrng::normal4(p.seed, id, k1, sdrng::kStreamNoise, static_cast<uint32_t>(lane + 64 * c), z[c]);
+    double lr = 0.0;
+    const double lu = sdrng::log_uniform(p.seed, id, k1);
+    bool reject = false;
+    if (j > 0) {                                           // position 1: the target gradient IS g0
+      gradient(dl);
+      double a1 = 0.0, a2 = 0.0;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          dl[c][e] = own[c][e] ? sqg2 * (dl[c][e] - g0[c][e]) : 0.0;
+          a1 = fma(static_cast<double>(z[c][e]), dl[c][e], a1);
+          a2 = fma(dl[c][e], dl[c][e], a2);
+        }
+      const double S1 = wave_sum(a1), S2 = wave_sum(a2);
+      lr = (-S1 - 0.5 * S2) * p.inv_tau;
+      reject = !(S2 == 0.0 || lu <= fmin(0.0, lr));
+      coef = S2 > 0.0 ? S1 / S2 : 0.0;
+    }
+    if (lane == 0) {
+      if (p.logratio) p.logratio[static_cast<int64_t>(b) * p.K + j] = static_cast<float>(lr);
+      if (p.logu) p.logu[static_cast<int64_t>(b) * p.K + j] = static_cast<float>(lu);
+    }
+    if (reject) {                                          // all lanes hold the same totals
+      jr = j;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (own[c][e])                                   // target gradient = g0 + Delta / sqrt(gamma/2)
+            cur[c][e] = cur[c][e] - gamma * (g0[c][e] + dl[c][e] / sqg2) +
+                        sq2g * (static_cast<double>(z[c][e]) - 2.0 * coef * dl[c][e]);
+      break;
+    }
+#pragma unroll
+    for (int c = 0; c < CPT; ++c)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (own[c][e]) cur[c][e] = cur[c][e] - gamma * g0[c][e] + sq2g * static_cast<double>(z[c][e]);
+  }
+
+  if (lane == 0) {
+    p.adv[b] = jr >= 0 ? jr + 1 : Kt;
+    if (p.rej) p.rej[b] = jr >= 0 ? 1 : 0;
+    const int jdone = jr >= 0 ? jr + 1 : Kt;
+    for (int j = jdone; j < p.K; ++j) {
+      if (p.logratio) p.logratio[static_cast<int64_t>(b) * p.K + j] = 0.f;
+      if (p.logu) p.logu[static_cast<int64_t>(b) * p.K + j] = 0.f;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int i0 = 4 * (lane + 64 * c);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (own[c][e]) p.x_out[static_cast<int64_t>(b) * d + i0 + e] = static_cast<float>(cur[c][e]);
+  }
+}
+
+template <int CPT>
+hipError_t launch_wave(const LangevinArgs& p, int dpad, hipStream_t st) {
+  const size_t shmem = sizeof(float) * kWaveM * static_cast<size_t>(dpad);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&langevin_window_wave_kernel<CPT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const unsigned grid = static_cast<unsigned>((p.B + kWaveChains - 1) / kWaveChains);
+  hipLaunchKernelGGL(langevin_window_wave_kernel<CPT>, dim3(grid), dim3(64 * kWaveChains), shmem, st, p, dpad);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 extern "C" int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
@@ -237,6 +491,18 @@ extern "C" int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const 
   p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.M = M; p.seed = ctx->seed;
   p.gamma = gamma; p.inv_s2 = 1.0 / (static_cast<double>(comp_std) * comp_std); p.inv_tau = 1.0 / ctx->tau;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  const int dpad = 4 * groups;
+  if (dpad <= 1024) {                       // a wavefront per chain, means in LDS (16 * dpad floats <= 64 KiB)
+    hipError_t e;
+    switch ((groups + 63) / 64) {
+      case 1: e = launch_wave<1>(p, dpad, st); break;
+      case 2: e = launch_wave<2>(p, dpad, st); break;
+      case 3: e = launch_wave<3>(p, dpad, st); break;
+      default: e = launch_wave<4>(p, dpad, st); break;
+    }
+    if (e != hipSuccess) return sdi::fail(ctx->err, SD_ERR_HIP, "sd_langevin_window: %s", hipGetErrorString(e));
+    return SD_OK;
+  }
   const dim3 grid(static_cast<unsigned>(B)), block(kThreads);
   switch (cpt) {
     case 1: hipLaunchKernelGGL((langevin_window_kernel<1, 16>), grid, block, 0, st, p); break;

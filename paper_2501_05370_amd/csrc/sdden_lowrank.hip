@@ -12,7 +12,7 @@
 // GEMM 1: P = X Q with the bracket applied per row in the epilogue (each row has its own step k);
 // GEMM 2: out = P' Q^T + g_perp(k) x + (1 - sqrt(ab_k) g_perp(k)) mu.
 //
-// Kernel: 128x128 output tile, K-step 16, 4 wavefronts (2x2) of 64x64 = 2x2 v_mfma_f32_32x32x2f32
+// Kernel: 128x128 (second GEMM) or 64x128 (first GEMM) output tile, K-step 16, 4 wavefronts (2x2) of 64x64 = 2x2 v_mfma_f32_32x32x2f32
 // tiles each; A is stored transposed in LDS so both operands are read with unit stride by the
 // 32 lanes of a k-slice; global->register prefetch of the next K-step overlaps the MFMAs.
 #include <hip/hip_runtime.h>
@@ -28,8 +28,8 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 16, kThreads = 256;
-constexpr int LDA = BM + 4, LDB = BN + 4;      // LDS row strides (floats)
+constexpr int BN = 128, BK = 16, kThreads = 256;
+constexpr int LDB = BN + 4;                    // LDS row stride of the B slice (floats)
 
 struct GemmArgs {
   const float* A;        // [*, lda] row-major; row r of the tile problem is A[arow(r)]
@@ -49,8 +49,13 @@ struct GemmArgs {
   const float *mu;       // [d]
 };
 
-template <int STAGE>
+// BM: rows per workgroup tile (64 or 128).  The first GEMM has only r/128 column tiles, so for
+// small row counts it uses 64-row tiles to put enough workgroups in flight.
+template <int STAGE, int BM>
 __global__ __launch_bounds__(kThreads) void lowrank_gemm_kernel(GemmArgs p) {
+  constexpr int LDA = BM + 4;
+  constexpr int TMI = BM / 64;                   // 32-row MFMA tiles per wavefront
+  constexpr int ACH = BM / 64;                   // float4 loads of A per thread per K-step
   __shared__ float As[2][BK][LDA];
   __shared__ float Bs[2][BK][LDB];
   const int M = *p.count;
@@ -60,49 +65,55 @@ __global__ __launch_bounds__(kThreads) void lowrank_gemm_kernel(GemmArgs p) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  // global -> LDS assignment: two float4 of A and two of B per thread per K-step
-  int a_m[2], a_k4[2], b_k[2], b_n4[2];
-  const float* a_src[2];
+  // global -> LDS assignment: ACH float4 of A and two of B per thread per K-step
+  int a_m[ACH], a_k4[ACH], b_k[2], b_n4[2];
+  const float* a_src[ACH];
   bool b_ok[2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < ACH; ++i) {
     const int idx = t + kThreads * i;
     a_m[i] = idx >> 2; a_k4[i] = idx & 3;
     const int gm = tile_m * BM + a_m[i];
     const int r = gm < M ? gm : M - 1;                       // clamp: rows past M are never stored
     const int src = (p.a_gather && p.rowidx) ? p.rowidx[r] : r;
     a_src[i] = p.A + static_cast<int64_t>(src) * p.lda + 4 * a_k4[i];
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int idx = t + kThreads * i;
     b_k[i] = idx >> 5; b_n4[i] = idx & 31;
     b_ok[i] = tile_n * BN + 4 * b_n4[i] < p.N;               // N is a multiple of 4
   }
   const float* b_src = p.Bm + tile_n * BN;
 
-  f32x16 acc[2][2];
+  f32x16 acc[TMI][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TMI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  float4 ra[2], rb[2];
+  float4 ra[ACH], rb[2];
   auto fetch = [&](int k0) {
 #pragma unroll
+    for (int i = 0; i < ACH; ++i) ra[i] = *reinterpret_cast<const float4*>(a_src[i] + k0);
+#pragma unroll
     for (int i = 0; i < 2; ++i) {
-      ra[i] = *reinterpret_cast<const float4*>(a_src[i] + k0);
       rb[i] = b_ok[i] ? *reinterpret_cast<const float4*>(b_src + static_cast<int64_t>(k0 + b_k[i]) * p.N + 4 * b_n4[i])
                       : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
   auto stash = [&](int s) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < ACH; ++i) {
       As[s][4 * a_k4[i] + 0][a_m[i]] = ra[i].x;
       As[s][4 * a_k4[i] + 1][a_m[i]] = ra[i].y;
       As[s][4 * a_k4[i] + 2][a_m[i]] = ra[i].z;
       As[s][4 * a_k4[i] + 3][a_m[i]] = ra[i].w;
-      *reinterpret_cast<float4*>(&Bs[s][b_k[i]][4 * b_n4[i]]) = rb[i];
     }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) *reinterpret_cast<float4*>(&Bs[s][b_k[i]][4 * b_n4[i]]) = rb[i];
   };
 
   const int nk = p.Kdim / BK;                                // Kdim is a multiple of BK (checked on host)
@@ -115,13 +126,13 @@ __global__ __launch_bounds__(kThreads) void lowrank_gemm_kernel(GemmArgs p) {
     if (kt + 1 < nk) fetch((kt + 1) * BK);
 #pragma unroll
     for (int k = 0; k < BK; k += 2) {
-      float a[2], b[2];
+      float a[TMI], b[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = As[s][k + half][wm * 64 + i * 32 + l32];
+      for (int i = 0; i < TMI; ++i) a[i] = As[s][k + half][wm * (BM / 2) + i * 32 + l32];
 #pragma unroll
       for (int j = 0; j < 2; ++j) b[j] = Bs[s][k + half][wn * 64 + j * 32 + l32];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TMI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
@@ -132,10 +143,10 @@ __global__ __launch_bounds__(kThreads) void lowrank_gemm_kernel(GemmArgs p) {
 
   // ---- epilogue.  acc[i][j][v] is element (row = (v/4)*8 + half*4 + v%4, col = l32) of its 32x32 tile
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < TMI; ++i) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int gm = tile_m * BM + wm * 64 + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+      const int gm = tile_m * BM + wm * (BM / 2) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
       if (gm >= M) continue;
       const int src = p.rowidx ? p.rowidx[gm] : gm;
       const int k = p.krow[src];
@@ -232,16 +243,18 @@ struct LowRankDenoiser final : sdden {
     GemmArgs a;
     a.rowidx = rowidx; a.count = count; a.krow = krow; a.X = X;
     a.gain = gain; a.sab = sab; a.gperp = gperp; a.coef = coef; a.qmu = qmu; a.mu = mu;
-    const int tiles_m = (R + BM - 1) / BM;
     // stage 1: P' = gain .* (X Q - sab qmu)       [M, rpad]
     a.A = X; a.lda = d; a.Bm = Q; a.N = rpad; a.Kdim = d; a.a_gather = 1; a.out = P;
     prof.mark(1, st);
-    hipLaunchKernelGGL(lowrank_gemm_kernel<1>, dim3(tiles_m * ((rpad + BN - 1) / BN)), dim3(kThreads), 0, st, a);
+    if (R <= 4096)   // few rows (the window-start call): smaller tiles put more workgroups in flight
+      hipLaunchKernelGGL((lowrank_gemm_kernel<1, 64>), dim3(((R + 63) / 64) * ((rpad + BN - 1) / BN)), dim3(kThreads), 0, st, a);
+    else
+      hipLaunchKernelGGL((lowrank_gemm_kernel<1, 128>), dim3(((R + 127) / 128) * ((rpad + BN - 1) / BN)), dim3(kThreads), 0, st, a);
     prof.mark(1, st);
     // stage 2: out = P' Q^T + gperp x + coef mu   [rows, d]
     a.A = P; a.lda = rpad; a.Bm = QT; a.N = d; a.Kdim = rpad; a.a_gather = 0; a.out = out;
     prof.mark(2, st);
-    hipLaunchKernelGGL(lowrank_gemm_kernel<2>, dim3(tiles_m * ((d + BN - 1) / BN)), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((lowrank_gemm_kernel<2, 128>), dim3(((R + 127) / 128) * ((d + BN - 1) / BN)), dim3(kThreads), 0, st, a);
     prof.mark(2, st);
     SD_HIP_TRY(err, hipGetLastError());
     return SD_OK;
