@@ -9,7 +9,8 @@
 // One wavefront per row.  Phase 1: a lane owns a component and walks the coordinates (no
 // cross-lane reduction for the logits).  Phase 2: a lane owns a coordinate and walks the
 // components.  All arithmetic in fp64: the rows are few and small, and the responsibilities are
-// exponentials of sums of d terms.
+// exponentials of sums of d terms.  Reciprocal variances use the fp32 hardware reciprocal refined by
+// two Newton steps in fp64 (relative error ~1e-14) instead of full fp64 divisions.
 #include <cmath>
 #include <new>
 #include <vector>
@@ -31,11 +32,20 @@ struct GmmArgs {
   const float *mu, *sd;      // [M,d]  component means and stds
   const float *muT, *sdT;    // [d,M]  the same, transposed
   const double* cst;         // [T,M]  log w_m - 1/2 sum_i log v_mi(k)
+  int Mp;                    // M rounded up to a power of two (<= 64), lanes per coordinate slice
   const float* ab;           // [T+1]
   const int32_t* active;
   int rows_per_chain;
   int R, d, M;
 };
+
+// 1/v for v in [~1e-3, ~1e3]: fp32 reciprocal, then y <- y (2 - v y) twice.
+__device__ __forceinline__ double reciprocal(double v) {
+  double y = static_cast<double>(__frcp_rn(static_cast<float>(v)));
+  y = y * fma(-v, y, 2.0);
+  y = y * fma(-v, y, 2.0);
+  return y;
+}
 
 __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_kernel(GmmArgs p) {
   extern __shared__ double smem[];
@@ -54,17 +64,37 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_kernel(
   __threadfence_block();
 
   double mx = -INFINITY;
-  for (int m = lane; m < p.M; m += 64) {
+  if (p.Mp < 64) {
+    // fewer than 64 components: 64/Mp lanes share a component and split the coordinates
+    const int m = lane % p.Mp, part = lane / p.Mp, parts = 64 / p.Mp;
     double q = 0.0;
-    for (int i = 0; i < p.d; ++i) {
-      const double diff = xs[i] - sab * p.muT[static_cast<int64_t>(i) * p.M + m];
-      const double sd = p.sdT[static_cast<int64_t>(i) * p.M + m];
-      const double v = ab * sd * sd + om;
-      q += diff * diff / v;
+    if (m < p.M) {
+      for (int i = part; i < p.d; i += parts) {
+        const double diff = xs[i] - sab * p.muT[static_cast<int64_t>(i) * p.M + m];
+        const double sd = p.sdT[static_cast<int64_t>(i) * p.M + m];
+        const double iv = reciprocal(ab * sd * sd + om);
+        q = fma(diff * diff, iv, q);
+      }
     }
-    const double logit = p.cst[static_cast<int64_t>(k) * p.M + m] - 0.5 * q;
-    rs[m] = logit;
-    mx = fmax(mx, logit);
+    for (int s = p.Mp; s < 64; s <<= 1) q += __shfl_xor(q, s, 64);
+    if (m < p.M && part == 0) {
+      const double logit = p.cst[static_cast<int64_t>(k) * p.M + m] - 0.5 * q;
+      rs[m] = logit;
+      mx = logit;
+    }
+  } else {
+    for (int m = lane; m < p.M; m += 64) {
+      double q = 0.0;
+      for (int i = 0; i < p.d; ++i) {
+        const double diff = xs[i] - sab * p.muT[static_cast<int64_t>(i) * p.M + m];
+        const double sd = p.sdT[static_cast<int64_t>(i) * p.M + m];
+        const double iv = reciprocal(ab * sd * sd + om);
+        q = fma(diff * diff, iv, q);
+      }
+      const double logit = p.cst[static_cast<int64_t>(k) * p.M + m] - 0.5 * q;
+      rs[m] = logit;
+      mx = fmax(mx, logit);
+    }
   }
   for (int s = 32; s >= 1; s >>= 1) mx = fmax(mx, __shfl_xor(mx, s, 64));
   double sum = 0.0;
@@ -86,8 +116,8 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_kernel(
       const double mu = p.mu[static_cast<int64_t>(m) * p.d + i];
       const double sd = p.sd[static_cast<int64_t>(m) * p.d + i];
       const double s2 = sd * sd;
-      const double v = ab * s2 + om;
-      acc += rs[m] * (mu + sab * s2 / v * (xi - sab * mu));
+      const double iv = reciprocal(ab * s2 + om);
+      acc += rs[m] * (mu + sab * s2 * iv * (xi - sab * mu));
     }
     o[i] = static_cast<float>(acc * inv);
   }
@@ -106,6 +136,8 @@ struct GmmDenoiser final : sdden {
     const size_t md = static_cast<size_t>(M) * d;
     p.X = X; p.krow = krow; p.out = out;
     p.mu = dev_f; p.sd = dev_f + md; p.muT = dev_f + 2 * md; p.sdT = dev_f + 3 * md; p.ab = dev_f + 4 * md;
+    p.Mp = 1;
+    while (p.Mp < M && p.Mp < 64) p.Mp <<= 1;
     p.cst = dev_cst; p.active = active; p.rows_per_chain = rows_per_chain;
     p.R = R; p.d = d; p.M = M;
     const size_t shmem = sizeof(double) * kRowsPerBlock * static_cast<size_t>(M + d);

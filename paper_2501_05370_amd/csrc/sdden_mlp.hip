@@ -11,10 +11,8 @@
 //   gemm<2>           H2 = silu(H1 W2 + b2)
 //   gemm<3>           out[rowidx[m]] = H2 W3 + b3          (fp32, scattered back to the source rows)
 //
-// GEMM kernel: C[M,N] = A[M,K] Bt[N,K]^T, both operands K-contiguous bf16.  Workgroup tile
-// BM x BN x 64 with 4 wavefronts (2x2), each wavefront (BM/2)x(BN/2) as 32x32 MFMA tiles.  LDS rows
-// are padded to 72 elements so the 16-byte fragment reads of 8 consecutive lanes cover all 32 banks.
-// The next K-slice is fetched into registers while the current one feeds the MFMAs.
+// The GEMM kernel (direct global->LDS loads, XOR-swizzled LDS rows, 32x32x16 bf16 MFMA tiles,
+// XCD-aware tile order) is in mlp_gemm.h.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
