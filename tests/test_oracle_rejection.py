@@ -157,3 +157,39 @@ def test_incorrect_mechanism_has_wrong_output_law():
     Yw, _, _ = incorrect_rejection(MP, MQ, S, ytil, u, rng.standard_normal((N, d)))
     assert stats.kstest((Yr[:, 0] - 3.0) / sigma, "norm").pvalue > 1e-4
     assert stats.kstest((Yw[:, 0] - 3.0) / sigma, "norm").pvalue < 1e-12
+
+
+def test_temperature_mean_shift_closed_form():
+    """App. "Influence of the temperature", Prop. "Link with guidance": E[Y] = m^q + C_tau (m^p - m^q)
+    with C_tau = 0 at tau = 1, < 0 below and > 0 above.  The expression printed for C_tau does not
+    reproduce the mechanism's mean (checked by Monte Carlo), so the pin is the closed form obtained
+    by integrating the algorithm directly along e = Delta/|Delta| (D = |Delta|, w0 = D(1/tau - 1/2),
+    c = exp(D^2 (1 - tau) / (2 tau^2))):
+        D C_tau = -2 phi(D/2) + D Phi(-D/2) + c [ 2 phi(w0) + D (1 - 2/tau) Phi(-w0) ]."""
+    rng = np.random.default_rng(8)
+    Phi, phi = stats.norm.cdf, stats.norm.pdf
+
+    def C(D, tau):
+        w0 = D * (1 / tau - 0.5)
+        c = np.exp(D * D * (1 - tau) / (2 * tau * tau))
+        return (-2 * phi(D / 2) + D * Phi(-D / 2) + c * (2 * phi(w0) + D * (1 - 2 / tau) * Phi(-w0))) / D
+
+    assert abs(C(1.3, 1.0)) < 1e-15
+    assert abs(C(0.7, 1e9) - 1.0) < 1e-6                       # tau -> infinity: Y ~ p, mean m^p
+    for tau in (0.5, 2.0, 4.0):
+        for d, sigma, dist in ((1, 0.5, 2.0), (3, 1.0, 1.0), (6, 2.0, 1.2)):
+            N = 1_000_000
+            mp = rng.standard_normal(d)
+            direction = rng.standard_normal(d)
+            mq = mp + dist * direction / np.linalg.norm(direction)
+            ytil, _, u = _draws(rng, mp, sigma, N)
+            Y, _, _ = reflection_rejection(np.broadcast_to(mp, (N, d)), np.broadcast_to(mq, (N, d)),
+                                           np.full(N, sigma), ytil, u, tau)
+            D = dist / sigma
+            shift = (Y.mean(0) - mq) @ (mp - mq) / dist ** 2     # component of E[Y] - m^q along m^p - m^q
+            se = sigma / dist / np.sqrt(N) * 2
+            assert abs(shift - C(D, tau)) < 5 * se, (tau, d, shift, C(D, tau))
+            assert (C(D, tau) < 0) == (tau < 1)
+            # nothing moves orthogonally to e
+            orth = (Y.mean(0) - mq) - shift * (mp - mq)
+            assert np.linalg.norm(orth) < 6 * sigma * np.sqrt(d / N)
