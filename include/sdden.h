@@ -66,8 +66,11 @@ int sdden_set_active_count(sdden* den, const int32_t* count /*dev*/, int32_t row
  * the evaluation's stream (gmm: 1 = posterior mean; lowrank: 1, 2 = the two GEMMs; mlp: 1..3 = the
  * three GEMMs; 0 = off, the default).  sdden_profile_collect waits for the recorded events, returns
  * the summed kernel time in ms and the number of timed launches, and starts a new collection.
- * Event objects are created on demand while profiling is on (never otherwise). */
+ * Event objects are created on demand while profiling is on (never otherwise).
+ * sdden_profile_min_rows restricts the timing to calls with R >= min_rows (default 0: every call),
+ * e.g. to the batched evaluation of the drafted states rather than the window-start call. */
 int sdden_profile(sdden* den, int32_t which);
+int sdden_profile_min_rows(sdden* den, int32_t min_rows);
 int sdden_profile_collect(sdden* den, double* total_ms, int64_t* launches);
 
 int sdden_destroy(sdden* den);

@@ -60,6 +60,7 @@ _SIGNATURES = {
     "sdden_eval": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]),
     "sdden_set_active_count": (c_int, [c_void_p, c_void_p, c_int32]),
     "sdden_profile": (c_int, [c_void_p, c_int32]),
+    "sdden_profile_min_rows": (c_int, [c_void_p, c_int32]),
     "sdden_profile_collect": (c_int, [c_void_p, POINTER(ctypes.c_double), POINTER(c_int64)]),
     "sdden_destroy": (c_int, [c_void_p]),
     "sdden_last_error": (c_char_p, [c_void_p]),
@@ -276,6 +277,9 @@ class Denoiser:
 
     def sdden_profile(self, which: int):
         self._check(self._lib.sdden_profile(self._h, which), "sdden_profile")
+
+    def sdden_profile_min_rows(self, min_rows: int):
+        self._check(self._lib.sdden_profile_min_rows(self._h, min_rows), "sdden_profile_min_rows")
 
     def sdden_profile_collect(self):
         ms, n = ctypes.c_double(), c_int64()

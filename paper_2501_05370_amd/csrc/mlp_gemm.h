@@ -7,9 +7,13 @@
 // wavefront load fills 1 KiB of LDS = 8 rows of a 64-element slice, lane l landing at byte 16*l;
 // bank conflicts are avoided by permuting which 16-byte chunk of its row a lane fetches
 // (chunk ^ row%8) instead of padding rows, so the 16-byte fragment reads of any 8 consecutive
-// rows cover all 32 banks.  Two LDS stages: the next slice streams in while the current one feeds
-// the MFMAs.  Tiles are ordered in PM x PN patches per XCD (workgroups go to the 8 XCDs
-// round-robin and each XCD has its own L2).
+// rows cover all 32 banks.  NS LDS stages form a ring: up to NS-1 slices stream in while the
+// current one feeds the MFMAs.  The per-slice workgroup barrier is a bare s_barrier behind
+// s_waitcnt vmcnt(n): __syncthreads() would drain every outstanding load and empty the ring.
+// The 256 x 256 tile fills LDS with two stages; the 128 x 128 tile used for few rows runs four,
+// which hides the load latency that otherwise bounds it (one workgroup per CU, half the CUs).
+// Tiles are ordered in PM x PN patches per XCD (workgroups go to the 8 XCDs round-robin and
+// each XCD has its own L2).
 // A must be readable for all rows of every launched tile (callers round their row capacity up to
 // kRowPad); rows >= M are computed on whatever is there and never stored.
 #pragma once
@@ -47,17 +51,33 @@ __device__ __forceinline__ uint16_t to_bf16_bits(float x) {
   return u;
 }
 
+// waits until at most N of this wavefront's vector-memory loads are outstanding (they complete in order)
+template <int N>
+__device__ __forceinline__ void wait_loads() {
+  static_assert(N == 0 || N == 4 || N == 6 || N == 8 || N == 12 || N == 16 || N == 24, "add the count");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+  if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+  if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  if constexpr (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+}
+
+// workgroup barrier that leaves vector-memory loads in flight (LDS traffic of this wavefront is drained)
+__device__ __forceinline__ void barrier_keep_loads() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // EPI 1: out = bf16(silu(acc + bias[krow[src]][n]));  EPI 2: out = bf16(silu(acc + bias[n]));
 // EPI 3: outf[src][n] = acc + bias[n].
-template <int BM, int BN, int WM, int WN, int EPI, int PM = 4, int PN = 8>
+template <int BM, int BN, int WM, int WN, int EPI, int NS, int PM = 4, int PN = 8>
 __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int APASS = BM / 8 / NW, BPASS = BN / 8 / NW;    // wavefront loads per K-slice
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "row groups must divide evenly");
   extern __shared__ __align__(1024) unsigned char smem[];
-  unsigned char* As = smem;                                  // [2][BM][128 B]
-  unsigned char* Bs = smem + 2 * BM * 128;                   // [2][BN][128 B]
+  unsigned char* As = smem;                                  // [NS][BM][128 B]
+  unsigned char* Bs = smem + NS * BM * 128;                  // [NS][BN][128 B]
 
   const int M = *p.count;
   const int tiles_n = p.N / BN;
@@ -107,15 +127,24 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   } while (0)
 
   const int nk = Kd / BK;
-  MLPGEMM_FETCH(0, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < NS - 1; ++k)
+    if (k < nk) MLPGEMM_FETCH(k, k * BK);
   // fragment addressing: row r, chunk c -> r*128 + ((c ^ (r & 7)) << 4); r & 7 == l32 & 7 for all tiles
   const int a_row = (wm * (BM / WM) + l32) * 128, b_row = (wn * (BN / WN) + l32) * 128;
   const int sw = l32 & 7;
   for (int kt = 0; kt < nk; ++kt) {
-    const int s = kt & 1;
-    if (kt + 1 < nk) MLPGEMM_FETCH(s ^ 1, (kt + 1) * BK);
+    const int s = kt % NS;
+    // slice kt has landed once only the NS-2 younger slices are outstanding; past the barrier every
+    // wavefront is done with slice kt-1, whose stage takes slice kt+NS-1
+    if (kt + NS - 1 < nk) {
+      wait_loads<(NS - 2) * (APASS + BPASS)>();
+      barrier_keep_loads();
+      MLPGEMM_FETCH((kt + NS - 1) % NS, (kt + NS - 1) * BK);
+    } else {
+      wait_loads<0>();
+      barrier_keep_loads();
+    }
     const unsigned char* Aw = As + s * BM * 128 + a_row;
     const unsigned char* Bw = Bs + s * BN * 128 + b_row;
 #pragma unroll
@@ -134,8 +163,6 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
   }
 #undef MLPGEMM_FETCH
 
@@ -158,12 +185,13 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int PM = 4, int PN = 8>
+template <int BM, int BN, int WM, int WN, int EPI, int NS, int PM = 4, int PN = 8>
 hipError_t launch(const Args& a, int Rmax, hipStream_t st) {
-  constexpr size_t shmem = 2 * static_cast<size_t>(BM + BN) * 128;
+  constexpr size_t shmem = NS * static_cast<size_t>(BM + BN) * 128;
+  static_assert(NS >= 2 && shmem <= 160 * 1024, "ring must fit the 160 KiB of LDS");
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, EPI, PM, PN>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, EPI, NS, PM, PN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -171,7 +199,7 @@ hipError_t launch(const Args& a, int Rmax, hipStream_t st) {
   const int tiles_m = (Rmax + BM - 1) / BM, tiles_n = a.N / BN;
   const int patches = ((tiles_m + PM - 1) / PM) * ((tiles_n + PN - 1) / PN);
   const int grid = (patches * PM * PN + 7) / 8 * 8;
-  hipLaunchKernelGGL((kernel<BM, BN, WM, WN, EPI, PM, PN>), dim3(grid), dim3(64 * WM * WN), shmem, st, a);
+  hipLaunchKernelGGL((kernel<BM, BN, WM, WN, EPI, NS, PM, PN>), dim3(grid), dim3(64 * WM * WN), shmem, st, a);
   return hipGetLastError();
 }
 

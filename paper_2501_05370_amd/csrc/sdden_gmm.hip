@@ -204,6 +204,7 @@ int sdden_eval(sdden* den, int32_t R, const float* X, const int32_t* krow, float
   if (!den) return SD_ERR_ARG;
   if (R < 0 || (R > 0 && (!X || !krow || !out))) return sdi::fail(den->err, SD_ERR_ARG, "sdden_eval: bad argument");
   if (R == 0) return SD_OK;
+  den->prof.cur_rows = R;
   return den->eval(R, X, krow, out, static_cast<hipStream_t>(stream));
 }
 
@@ -217,6 +218,12 @@ int sdden_profile(sdden* den, int32_t which) {
   if (!den || which < 0) return SD_ERR_ARG;
   den->prof.which = which;
   den->prof.used = 0;
+  return SD_OK;
+}
+
+int sdden_profile_min_rows(sdden* den, int32_t min_rows) {
+  if (!den || min_rows < 0) return SD_ERR_ARG;
+  den->prof.min_rows = min_rows;
   return SD_OK;
 }
 

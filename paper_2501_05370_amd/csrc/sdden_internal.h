@@ -12,13 +12,14 @@
 // HIP-event timing of one chosen kernel inside sdden_eval (measurement only; off by default).
 struct sdden_profiler {
   int which = 0;                       // 0 = off, else the 1-based index of the timed kernel
+  int min_rows = 0, cur_rows = 0;      // only calls with at least min_rows rows are timed
   std::vector<hipEvent_t> events;      // start/stop pairs, reused between collections
   size_t used = 0;
   ~sdden_profiler() {
     for (hipEvent_t e : events) (void)hipEventDestroy(e);
   }
   void mark(int kernel_index, hipStream_t st) {
-    if (which != kernel_index) return;
+    if (which != kernel_index || cur_rows < min_rows) return;
     if (used == events.size()) {
       hipEvent_t e;
       if (hipEventCreate(&e) != hipSuccess) return;

@@ -58,11 +58,21 @@ float bf16_bits_to_float(uint16_t b) {
   return f;
 }
 
-// Large row counts: 256x256 tile, 8 wavefronts (2x4); small ones (the window-start call): 128x128,
-// 4 wavefronts, so that more workgroups are in flight.
+// Tile choice by how well the launch fills the 256 CUs.  The 256x256 tile (8 wavefronts, two LDS
+// stages) has the highest rate per CU and is taken when its last round of workgroups is at least
+// three quarters full; otherwise 128x128 (4 wavefronts, two stages, two workgroups per CU) when
+// that gives 512 tiles or more, else 64x128: with at most one workgroup per CU (the window-start
+// call) as a four-stage ring, with more as two stages so that three workgroups share a CU.
 template <int EPI>
 int launch_gemm(const mlpgemm::Args& a, int R, hipStream_t st, std::string& err) {
-  hipError_t e = R > 1024 ? mlpgemm::launch<256, 256, 2, 4, EPI>(a, R, st) : mlpgemm::launch<128, 128, 2, 2, EPI>(a, R, st);
+  const int t256 = ((R + 255) / 256) * (a.N / 256);
+  const int t128 = ((R + 127) / 128) * (a.N / 128);
+  const int t64 = ((R + 63) / 64) * (a.N / 128);
+  hipError_t e;
+  if (4 * t256 >= 3 * ((t256 + 255) / 256) * 256) e = mlpgemm::launch<256, 256, 2, 4, EPI, 2>(a, R, st);
+  else if (t128 >= 512) e = mlpgemm::launch<128, 128, 2, 2, EPI, 2>(a, R, st);
+  else if (t64 > 256) e = mlpgemm::launch<64, 128, 2, 2, EPI, 2>(a, R, st);
+  else e = mlpgemm::launch<64, 128, 2, 2, EPI, 4>(a, R, st);
   if (e != hipSuccess) return sdi::fail(err, SD_ERR_HIP, "mlp gemm launch: %s", hipGetErrorString(e));
   return SD_OK;
 }
