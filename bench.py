@@ -128,6 +128,57 @@ def run_gpu(cfg, steps, warmup, stages):
     return elapsed, counters, roofline, stage_table
 
 
+def run_context(cfg):
+    """Untimed extras around the headline figure: the acceptance rate per window position (one more
+    sampler pass with a per-window tally), the target calls per chain step in the paper's sense (one
+    call = one batched evaluation, whatever its row count) and the plain sequential chain on the same
+    GPU (the same sampler with a window of one step, which accepts trivially)."""
+    import torch
+    import workloads as W
+    from paper_2501_05370_amd.runner import make_sampler
+
+    K, T = cfg.K, cfg.T
+    smp = make_sampler(cfg)
+    b = smp.buf
+    ids = torch.arange(cfg.B, dtype=torch.int64, device="cuda")
+    smp.ctx.sd_set_seed(cfg.seed)
+    B = smp.start(ids, True)
+    j = torch.arange(1, K + 1, device="cuda")
+    reached = torch.zeros(K, dtype=torch.int64, device="cuda")
+    accepted = torch.zeros(K, dtype=torch.int64, device="cuda")
+    windows = 0
+    while B > 0:
+        n0 = b.n[:B].clone()
+        smp.window(B)
+        Kt = torch.clamp(T - n0, max=K).to(torch.int64)
+        nacc = (b.adv[:B].to(torch.int64) - b.rejected[:B].to(torch.int64))[:, None]   # accepted drafts
+        r = (Kt[:, None] >= j) & (nacc >= j - 1)
+        reached += r.sum(0)
+        accepted += (r & (nacc >= j)).sum(0)
+        smp.advance(B)
+        B = int(b.B_active.item())
+        windows += 1
+    rate = (accepted.double() / reached.clamp(min=1).double()).tolist()
+    calls = windows * (2 if (cfg.kind != "langevin" and K > 1) else 1)
+    out = {"acceptance_rate_by_position": [round(x, 4) for x in rate],
+           "target_calls_per_pass": calls, "chain_steps_per_target_call": round(T / calls, 3)}
+    del smp
+    seq_cfg = W.make_config(cfg.name, K=1)
+    seq = make_sampler(seq_cfg)
+    seq.ctx.sd_set_seed(cfg.seed)
+    seq.run(ids)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    seq.ctx.sd_set_seed(cfg.seed + 1)
+    _, c = seq.run(ids)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    out["sequential_gpu"] = {"value": round(c[0] / dt, 1), "unit": "diffusion steps/s", "ms_per_pass": round(1e3 * dt, 3),
+                             "target_calls_per_pass": c[3],
+                             "note": "same kernels with a window of one step: T sequential target calls per chain"}
+    return out
+
+
 def cpu_baseline(cfg, budget_s=15.0):
     """Time the oracle on a bounded sample of the workload: a subset of the chains, run window by
     window until the time budget is used or the chains finish."""
@@ -189,6 +240,8 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(DESCRIPTIONS))
     ap.add_argument("--stages", action="store_true", help="time every stage (adds event overhead)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the untimed extras (acceptance by position, sequential chain on the GPU)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprof FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -230,6 +283,8 @@ def main():
     }
     if stage_table:
         line["stages"] = stage_table
+    if not args.no_context:
+        line["context"] = run_context(cfg)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(line))
