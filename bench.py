@@ -82,7 +82,15 @@ def roofline_plan(cfg):
     raise ValueError(cfg.kind)
 
 
-def run_gpu(cfg, steps, warmup, stages):
+def _sampler(cfg, drafter):
+    import workloads as W
+    from paper_2501_05370_amd.runner import make_sampler
+    if drafter == "independent":
+        return make_sampler(cfg, drafter="independent", draft_params=W.draft_params(cfg))
+    return make_sampler(cfg)
+
+
+def run_gpu(cfg, steps, warmup, stages, drafter="frozen"):
     import torch
     from paper_2501_05370_amd.runner import make_sampler
     from paper_2501_05370_amd.sampler import StageTimer
@@ -90,7 +98,7 @@ def run_gpu(cfg, steps, warmup, stages):
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU (the HIP library has no CPU fallback)")
     torch.cuda.set_device(0)
-    smp = make_sampler(cfg)
+    smp = _sampler(cfg, drafter)
     ids = torch.arange(cfg.B, dtype=torch.int64, device="cuda")
     plan = roofline_plan(cfg)
     for w in range(warmup):
@@ -134,7 +142,7 @@ def run_gpu(cfg, steps, warmup, stages):
     return elapsed, counters, roofline, stage_table
 
 
-def run_context(cfg):
+def run_context(cfg, drafter="frozen"):
     """Untimed extras around the headline figure: the acceptance rate per window position (one more
     sampler pass with a per-window tally), the target calls per chain step in the paper's sense (one
     call = one batched evaluation, whatever its row count) and the plain sequential chain on the same
@@ -144,7 +152,7 @@ def run_context(cfg):
     from paper_2501_05370_amd.runner import make_sampler
 
     K, T = cfg.K, cfg.T
-    smp = make_sampler(cfg)
+    smp = _sampler(cfg, drafter)
     b = smp.buf
     ids = torch.arange(cfg.B, dtype=torch.int64, device="cuda")
     smp.ctx.sd_set_seed(cfg.seed)
@@ -185,7 +193,7 @@ def run_context(cfg):
     return out
 
 
-def cpu_baseline(cfg, budget_s=15.0):
+def cpu_baseline(cfg, budget_s=15.0, drafter="frozen"):
     """Time the oracle on a bounded sample of the workload: a subset of the chains, run window by
     window until the time budget is used or the chains finish."""
     import workloads as W
@@ -210,6 +218,12 @@ def cpu_baseline(cfg, budget_s=15.0):
         D, cores = MLPDenoiser(cfg.params), blas_threads
     else:
         D, cores = GMMScore(cfg.params), 1
+    kw = {}
+    if drafter == "independent":
+        dp = W.draft_params(cfg)
+        Dd = {"gmm": lambda: GMMDenoiser(dp, sched.alpha_bar_state), "lowrank": lambda: LowRankDenoiser(dp, sched.alpha_bar_state),
+              "mlp": lambda: MLPDenoiser(dp)}[cfg.kind]()
+        kw = dict(drafter="independent", D_draft=Dd)
     ids0 = ids
     out = np.zeros((nchains, cfg.d))
     steps_done = windows = runs = 0
@@ -225,7 +239,7 @@ def cpu_baseline(cfg, budget_s=15.0):
             if cfg.kind == "langevin":
                 y_out, adv, _, _, _ = L.ula_window(D, y, n, ids, cfg.K, cfg.T, cfg.gamma, seed)
             else:
-                res, *_ = S.window(sched, D, y, n, ids, cfg.K, seed)
+                res, *_ = S.window(sched, D, y, n, ids, cfg.K, seed, **kw)
                 y_out, adv = res.y_out, res.adv
             steps_done += int(adv.sum())
             windows += 1
@@ -245,6 +259,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(DESCRIPTIONS))
     ap.add_argument("--stages", action="store_true", help="time every stage (adds event overhead)")
+    ap.add_argument("--drafter", default="frozen", choices=["frozen", "independent"],
+                    help="frozen (default, the benchmark's drafter) or the independent draft model: a cheaper "
+                         "network of the same family called at every window position (c1-c4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the untimed extras (acceptance by position, sequential chain on the GPU)")
@@ -266,7 +283,9 @@ def main():
     import workloads as W
     cfg = W.make_config(args.workload)
     steps = args.steps if args.steps is not None else {"c1": 20, "c2": 10, "c3": 3, "c4": 3, "c5": 2}[cfg.name]
-    elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages)
+    if args.drafter == "independent" and cfg.kind == "langevin":
+        raise SystemExit("bench.py: the independent drafter is built for the diffusion workloads c1-c4")
+    elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages, args.drafter)
     total_steps = counters[0]
     assert total_steps == cfg.B * cfg.T * steps, (total_steps, cfg.B, cfg.T, steps)
     line = {
@@ -278,7 +297,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.kind == "mlp" else "f32", "data": "synthetic",
         "config": {"workload": DESCRIPTIONS[cfg.name], "chains": cfg.B, "d": cfg.d, "window_K": cfg.K,
-                   "chain_steps_T": cfg.T, "drafter": "frozen", "seed": cfg.seed,
+                   "chain_steps_T": cfg.T, "drafter": args.drafter, "seed": cfg.seed,
                    "step_definition": "one full sampler pass: all chains from step 0 to T"},
         "mean_accepted_draft_length": round(counters[0] / max(1, counters[1]), 4),
         "windows_per_step": round(counters[3] / steps, 2),
@@ -290,9 +309,9 @@ def main():
     if stage_table:
         line["stages"] = stage_table
     if not args.no_context:
-        line["context"] = run_context(cfg)
+        line["context"] = run_context(cfg, args.drafter)
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg)
+        line["cpu_baseline"] = cpu_baseline(cfg, drafter=args.drafter)
     print(json.dumps(line))
 
 

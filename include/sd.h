@@ -83,6 +83,11 @@ int sd_set_temperature(sd_ctx* ctx, float tau);
  * only the first min(B, *count) chains as present, so a fixed launch sequence (for instance a
  * captured HIP graph) keeps working while sd_advance shrinks the batch.  NULL restores B.        */
 int sd_set_active_count(sd_ctx* ctx, const int32_t* count);
+/* EXPLICIT mode only, optional: the target prediction at the window start, D(y_n, n), as its own
+ * [B,d] array (dev).  When set, sd_verify reads it wherever it would read row 0 of Dq, so the
+ * window-start call and the batched call on the drafts can write to separate dense outputs.
+ * NULL (default) restores row 0 of Dq. */
+int sd_set_start_prediction(sd_ctx* ctx, const float* D_start);
 
 /* Scratch for sd_advance (compaction map): bytes needed for batches up to Bmax, and the buffer. */
 size_t sd_workspace_bytes(const sd_ctx* ctx, int32_t Bmax);
@@ -103,6 +108,22 @@ int sd_init_state(sd_ctx* ctx, int32_t B, const int64_t* chain_id, float* y, int
  *      not evaluated.                                                                    (dev) */
 int sd_draft(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int64_t* chain_id,
              const float* D0, float* Ytilde, int32_t* krow, void* stream);
+
+/* One position of a drafter that calls a (cheaper) network at every position: the independent
+ * draft model of Sec. 3.1, p(y_{k+1} | y_k) = N(a_k y_k + c_k D^p(y_k, k), sigma_k^2 I).
+ * For window position j (1-based), k = n+j-1, and every chain with j <= Kt:
+ *     mp[b][j-1] = a[k] prev[b] + c[k] Dp[b];   Ytilde[b][j-1] = mp[b][j-1] + sigma[k] z_{k+1}
+ * with the same keyed noise as sd_draft; rows of chains with j > Kt are zero-filled.
+ * in : prev [B,d] = y~_{n+j-1} (y for j = 1); Dp [B,d] = D^p(prev, n+j-1); n, chain_id       (dev)
+ * out: mp, Ytilde [B,K,d] (row j-1 only); krow [B,K] (entry j-1, as in sd_draft);
+ *      next [B,d] or NULL: the new state as a dense matrix (must not alias prev or Dp);
+ *      knext [B] or NULL: its step index n+j, or -1 when j >= Kt (the row needs no further call):
+ *      (next, knext) are the input of the drafter's call for position j+1.                  (dev)
+ * The caller loops j = 1..K, calling its draft network between the steps, then the target on
+ * (Ytilde, krow) and sd_verify in EXPLICIT mode with mp. */
+int sd_draft_step(sd_ctx* ctx, int32_t B, int32_t j, const float* prev, const int32_t* n,
+                  const int64_t* chain_id, const float* Dp, float* mp, float* Ytilde, int32_t* krow,
+                  float* next, int32_t* knext, void* stream);
 
 /* Accept test + first rejection + reflection (Alg. "REJECTION ... same covariance"; detailed
  * algorithm, second for-loop).  For j = 1 .. Kt, k = n+j-1, prev = y (j = 1) or Ytilde[j-2]:

@@ -44,6 +44,8 @@ _SIGNATURES = {
     "sd_set_workspace": (c_int, [c_void_p, c_void_p, c_size_t]),
     "sd_init_state": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]),
     "sd_draft": (c_int, [c_void_p, c_int32] + [c_void_p] * 7),
+    "sd_draft_step": (c_int, [c_void_p, c_int32, c_int32] + [c_void_p] * 10),
+    "sd_set_start_prediction": (c_int, [c_void_p, c_void_p]),
     "sd_verify": (c_int, [c_void_p, c_int32] + [c_void_p] * 12),
     "sd_advance": (c_int, [c_void_p, c_int32] + [c_void_p] * 10),
     "sd_langevin_window": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -161,6 +163,11 @@ class Context:
         self._keep_count = count
         self._check(self._lib.sd_set_active_count(self._h, ptr), "sd_set_active_count")
 
+    def sd_set_start_prediction(self, D_start: Optional[torch.Tensor]):
+        ptr = _dev(D_start, torch.float32, "D_start", allow_none=True)
+        self._keep_start = D_start
+        self._check(self._lib.sd_set_start_prediction(self._h, ptr), "sd_set_start_prediction")
+
     def sd_workspace_bytes(self, Bmax: int) -> int:
         return int(self._lib.sd_workspace_bytes(self._h, Bmax))
 
@@ -185,6 +192,14 @@ class Context:
                                        _dev(chain_id, torch.int64, "chain_id"), _dev(D0, torch.float32, "D0"),
                                        _dev(Ytilde, torch.float32, "Ytilde"), _dev(krow, torch.int32, "krow"),
                                        _stream()), "sd_draft")
+
+    def sd_draft_step(self, B, j, prev, n, chain_id, Dp, mp, Ytilde, krow, next=None, knext=None):
+        self._check(self._lib.sd_draft_step(
+            self._h, B, j, _dev(prev, torch.float32, "prev"), _dev(n, torch.int32, "n"),
+            _dev(chain_id, torch.int64, "chain_id"), _dev(Dp, torch.float32, "Dp"),
+            _dev(mp, torch.float32, "mp"), _dev(Ytilde, torch.float32, "Ytilde"),
+            _dev(krow, torch.int32, "krow"), _dev(next, torch.float32, "next", True),
+            _dev(knext, torch.int32, "knext", True), _stream()), "sd_draft_step")
 
     def sd_verify(self, B, y, n, chain_id, D0_or_mp, Dq, Ytilde, y_out, adv, rejected=None,
                   logratio=None, logu=None):

@@ -18,6 +18,7 @@ struct sd_ctx {
   float* dev_c = nullptr;
   float* dev_sigma = nullptr;
   const int32_t* active = nullptr;
+  const float* start_pred = nullptr;   // EXPLICIT mode: D(y_n, n) as [B,d], replaces row 0 of Dq
   void* ws = nullptr;
   size_t ws_bytes = 0;
   int device = 0;

@@ -148,6 +148,86 @@ __global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// One position of a drafter that needs a network call per position (the independent draft model
+// of Sec. 3.1): m^p = a_k prev + c_k D^p(prev, k), y~ = m^p + sigma_k z_{k+1}, k = n + j - 1.
+// Same thread-per-Philox-block mapping and noise keys as the frozen rollout.  Besides the window
+// rows it writes the new state as a dense [B,d] matrix and its step index, the input of the
+// drafter's next call (index -1 once the chain's window has ended).
+// ---------------------------------------------------------------------------------------------
+struct DraftStepArgs {
+  const float *prev, *Dp;
+  const int32_t* n;
+  const int64_t* id;
+  float *mp, *Ytil, *next;
+  int32_t *krow, *knext;
+  const float *a, *c, *sigma;
+  const int32_t* active;
+  int B, d, K, T, nblk, j;
+  uint64_t seed;
+};
+
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void draft_step_kernel(DraftStepArgs p) {
+  const int64_t g = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  const int Bact = active_chains(p.active, p.B);
+  if (g >= static_cast<int64_t>(Bact) * p.nblk) return;
+  const int b = static_cast<int>(g / p.nblk);
+  const int blk = static_cast<int>(g % p.nblk);
+  const int i0 = 4 * blk;
+  const int n = p.n[b];
+  const int Kt = min(p.K, p.T - n);
+  const int j = p.j;                                  // 1-based window position
+  float m[4] = {0.f, 0.f, 0.f, 0.f}, out[4] = {0.f, 0.f, 0.f, 0.f};
+  const int64_t row = static_cast<int64_t>(b) * p.d + i0;
+  if (j <= Kt) {
+    const int k = n + j - 1;
+    const float a = p.a[k], c = p.c[k], s = p.sigma[k];
+    float pv[4], dp[4], z[4];
+    if (VEC == 4) {
+      Pack<4> t;
+      t.load(p.prev + row);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pv[e] = t.v[e];
+      t.load(p.Dp + row);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dp[e] = t.v[e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool in = i0 + e < p.d;
+        pv[e] = in ? p.prev[row + e] : 0.f;
+        dp[e] = in ? p.Dp[row + e] : 0.f;
+      }
+    }
+    sdrng::normal4(p.seed, p.id[b], static_cast<uint32_t>(k + 1), sdrng::kStreamNoise, static_cast<uint32_t>(blk), z);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      m[e] = fmaf(a, pv[e], c * dp[e]);
+      out[e] = fmaf(s, z[e], m[e]);
+    }
+  }
+  const int64_t w = (static_cast<int64_t>(b) * p.K + (j - 1)) * p.d + i0;
+  if (VEC == 4) {
+    *reinterpret_cast<float4*>(p.mp + w) = make_float4(m[0], m[1], m[2], m[3]);
+    *reinterpret_cast<float4*>(p.Ytil + w) = make_float4(out[0], out[1], out[2], out[3]);
+    if (p.next) *reinterpret_cast<float4*>(p.next + row) = make_float4(out[0], out[1], out[2], out[3]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (i0 + e < p.d) {
+        p.mp[w + e] = m[e];
+        p.Ytil[w + e] = out[e];
+        if (p.next) p.next[row + e] = out[e];
+      }
+  }
+  if (blk == 0) {
+    const int kn = (j <= Kt - 1) ? n + j : -1;
+    p.krow[static_cast<int64_t>(b) * p.K + (j - 1)] = kn;
+    if (p.knext) p.knext[b] = kn;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Accept test, first rejection, reflection.
 //
 // TPC threads cooperate on one chain (kBlock/TPC chains per workgroup).  Pass 1 streams the
@@ -162,6 +242,7 @@ __global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
 // ---------------------------------------------------------------------------------------------
 struct VerifyArgs {
   const float *y, *D0mp, *Dq, *Ytil;
+  const float* Dq0;            // EXPLICIT mode, optional: row 0 of Dq kept as a separate [B,d] array
   const int32_t* n;
   const int64_t* id;
   float* y_out;
@@ -231,7 +312,8 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
             if (FROZEN) {
               if (j > 0) dq.load(p.Dq + r);
             } else {
-              dq.load(p.Dq + r);
+              if (j == 0 && p.Dq0) dq.load(p.Dq0 + rowB + off);
+              else dq.load(p.Dq + r);
               mp.load(p.D0mp + r);
             }
 #pragma unroll
@@ -354,7 +436,8 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
     Pack<VEC> prev, cur, dq, x, o;
     prev.load(prevrow + off);
     cur.load(p.Ytil + r + off);
-    dq.load(p.Dq + r + off);
+    if (!FROZEN && jr == 0 && p.Dq0) dq.load(p.Dq0 + rowB + off);
+    else dq.load(p.Dq + r + off);
     if (FROZEN) x.load(p.D0mp + rowB + off);
     else x.load(p.D0mp + r + off);
 #pragma unroll
@@ -553,6 +636,12 @@ int sd_set_temperature(sd_ctx* ctx, float tau) {
   return SD_OK;
 }
 
+int sd_set_start_prediction(sd_ctx* ctx, const float* D_start) {
+  if (!ctx) return SD_ERR_ARG;
+  ctx->start_pred = D_start;
+  return SD_OK;
+}
+
 int sd_set_active_count(sd_ctx* ctx, const int32_t* count) {
   if (!ctx) return SD_ERR_ARG;
   ctx->active = count;
@@ -614,6 +703,32 @@ int sd_draft(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int
   return SD_OK;
 }
 
+int sd_draft_step(sd_ctx* ctx, int32_t B, int32_t j, const float* prev, const int32_t* n, const int64_t* chain_id,
+                  const float* Dp, float* mp, float* Ytilde, int32_t* krow, float* next, int32_t* knext,
+                  void* stream) {
+  if (int rc = check_ctx(ctx)) return rc;
+  if (B < 0 || j < 1 || j > ctx->K || (B > 0 && (!prev || !n || !chain_id || !Dp || !mp || !Ytilde || !krow)))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_draft_step: bad argument (j must be in 1..K)");
+  if (next && (next == prev || next == Dp))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_draft_step: next must not alias prev or Dp");
+  if (B == 0) return SD_OK;
+  DraftStepArgs p;
+  p.prev = prev; p.Dp = Dp; p.n = n; p.id = chain_id; p.mp = mp; p.Ytil = Ytilde; p.next = next;
+  p.krow = krow; p.knext = knext;
+  p.a = ctx->dev_a; p.c = ctx->dev_c; p.sigma = ctx->dev_sigma; p.active = ctx->active;
+  p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.nblk = (ctx->d + 3) / 4; p.j = j; p.seed = ctx->seed;
+  const int64_t total = static_cast<int64_t>(B) * p.nblk;
+  const int64_t grid = (total + kBlock - 1) / kBlock;
+  if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_draft_step: B*d too large");
+  const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(prev) && sdi::aligned16(Dp) && sdi::aligned16(mp) &&
+                   sdi::aligned16(Ytilde) && sdi::aligned16(next);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (vec) hipLaunchKernelGGL(draft_step_kernel<4>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st, p);
+  else     hipLaunchKernelGGL(draft_step_kernel<1>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st, p);
+  SD_HIP_TRY(ctx->err, hipGetLastError());
+  return SD_OK;
+}
+
 int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int64_t* chain_id,
               const float* D0_or_mp, const float* Dq, const float* Ytilde, float* y_out,
               int32_t* adv, uint8_t* rejected, float* logratio, float* logu, void* stream) {
@@ -624,10 +739,11 @@ int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const in
   VerifyArgs p;
   p.y = y; p.D0mp = D0_or_mp; p.Dq = Dq; p.Ytil = Ytilde; p.n = n; p.id = chain_id;
   p.y_out = y_out; p.adv = adv; p.rej = rejected; p.logratio = logratio; p.logu = logu;
+  p.Dq0 = ctx->mode == SD_DRAFT_EXPLICIT ? ctx->start_pred : nullptr;
   p.a = ctx->dev_a; p.c = ctx->dev_c; p.sigma = ctx->dev_sigma; p.active = ctx->active;
   p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.seed = ctx->seed; p.inv_tau = 1.0 / ctx->tau;
   const bool frozen = ctx->mode == SD_DRAFT_FROZEN;
-  const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y) && sdi::aligned16(D0_or_mp) &&
+  const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y) && sdi::aligned16(D0_or_mp) && sdi::aligned16(p.Dq0) &&
                    sdi::aligned16(Dq) && sdi::aligned16(Ytilde) && sdi::aligned16(y_out);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int ncol = vec ? ctx->d / 4 : ctx->d;

@@ -4,7 +4,7 @@ from __future__ import annotations
 import torch
 
 from .binding import Context, Denoiser
-from .sampler import DiffusionSampler, LangevinSampler
+from .sampler import DiffusionSampler, IndependentDrafterSampler, LangevinSampler
 
 
 def make_context(cfg, seed=None) -> Context:
@@ -14,8 +14,8 @@ def make_context(cfg, seed=None) -> Context:
     return ctx
 
 
-def make_denoiser(cfg, max_rows: int) -> Denoiser:
-    p, s = cfg.params, cfg.schedule
+def make_denoiser(cfg, max_rows: int, params=None) -> Denoiser:
+    p, s = (cfg.params if params is None else params), cfg.schedule
     if cfg.kind == "gmm":
         return Denoiser.sdden_gmm_create(p.means, p.stds, p.logw, s.alpha_bar_state)
     if cfg.kind == "lowrank":
@@ -27,10 +27,19 @@ def make_denoiser(cfg, max_rows: int) -> Denoiser:
     raise ValueError(f"no denoiser for workload kind {cfg.kind!r}")
 
 
-def make_sampler(cfg, B=None, out_rows=None, seed=None):
-    """A sampler for up to B chains of configuration ``cfg`` on the current device."""
+def make_sampler(cfg, B=None, out_rows=None, seed=None, drafter: str = "frozen", draft_params=None):
+    """A sampler for up to B chains of configuration ``cfg`` on the current device.  ``drafter`` is
+    "frozen" (default) or "independent" with the draft model's parameters in ``draft_params``."""
     B = cfg.B if B is None else B
     ctx = make_context(cfg, seed)
+    if drafter == "independent":
+        if cfg.kind == "langevin" or draft_params is None:
+            raise ValueError("the independent drafter needs a diffusion workload and draft_params")
+        den = make_denoiser(cfg, B * cfg.K)
+        draft = make_denoiser(cfg, B, draft_params)
+        return IndependentDrafterSampler(ctx, den, draft, B, out_rows)
+    if drafter != "frozen":
+        raise ValueError(drafter)
     if cfg.kind == "langevin":
         p = cfg.params
         dev = lambda a: torch.as_tensor(a, dtype=torch.float32).cuda().contiguous()

@@ -131,6 +131,42 @@ class DiffusionSampler(_SamplerBase):
             ctx.sd_verify(B, b.y, b.n, b.chain_id, b.D0, b.Dq, b.Ytilde, b.y_out, b.adv, b.rejected, lr, lu)
 
 
+class IndependentDrafterSampler(_SamplerBase):
+    """The same loop with the independent draft model of Sec. 3.1: a cheaper network ``draft_den`` is
+    called once per window position (``sd_draft_step`` between the calls), then the target runs once
+    on all drafted states and ``sd_verify`` works in EXPLICIT mode on the stored draft means."""
+
+    def __init__(self, ctx: Context, den: Denoiser, draft_den: Denoiser, B: int, out_rows: Optional[int] = None):
+        from .binding import SD_DRAFT_EXPLICIT
+        self.den, self.draft_den = den, draft_den
+        self._setup(ctx, B, out_rows, True)
+        b, f32 = self.buf, dict(dtype=torch.float32, device="cuda")
+        b.mp = torch.zeros(B, ctx.K, ctx.d, **f32)
+        b.Dp = torch.zeros(B, ctx.d, **f32)
+        b.cur = [torch.zeros(B, ctx.d, **f32), torch.zeros(B, ctx.d, **f32)]
+        b.kcur = [torch.full((B,), -1, dtype=torch.int32, device="cuda") for _ in range(2)]
+        ctx.sd_set_draft_mode(SD_DRAFT_EXPLICIT)
+        ctx.sd_set_start_prediction(b.D0)
+
+    def window(self, B: int, diagnostics=None):
+        b, ctx, d, K, t = self.buf, self.ctx, self.ctx.d, self.ctx.K, self.timer
+        with t.stage("predict_start", B):
+            self.den.sdden_eval(B, b.y, b.n, b.D0)              # target at the window start
+        prev, kprev = b.y, b.n
+        with t.stage("draft", B):
+            for j in range(1, K + 1):
+                self.draft_den.sdden_eval(B, prev, kprev, b.Dp)
+                nxt, knext = b.cur[j & 1], b.kcur[j & 1]
+                ctx.sd_draft_step(B, j, prev, b.n, b.chain_id, b.Dp, b.mp, b.Ytilde, b.krow, nxt, knext)
+                prev, kprev = nxt, knext
+        if K > 1:
+            with t.stage("predict_drafts", B):
+                self.den.sdden_eval(B * K, b.Ytilde.view(-1, d), b.krow.view(-1), b.Dq.view(-1, d)[1:])
+        lr, lu = diagnostics if diagnostics is not None else (None, None)
+        with t.stage("verify", B):
+            ctx.sd_verify(B, b.y, b.n, b.chain_id, b.mp, b.Dq, b.Ytilde, b.y_out, b.adv, b.rejected, lr, lu)
+
+
 class LangevinSampler(_SamplerBase):
     def __init__(self, ctx: Context, means: torch.Tensor, logw: torch.Tensor, comp_std: float,
                  gamma: float, B: int, out_rows: Optional[int] = None):

@@ -196,6 +196,27 @@ class Config:
     extra: Dict[str, object] = field(default_factory=dict)
 
 
+def draft_params(cfg: "Config"):
+    """Parameters of a cheaper draft model of the same family as the target (input preparation
+    for the independent drafter of Sec. 3.1; no claim of a trained fit):
+    gmm      every second component of the mixture, weights renormalised;
+    lowrank  the first quarter of the columns of U, the dropped variance spread over s2;
+    mlp      a separately drawn MLP of a quarter of the hidden width."""
+    p = cfg.params
+    if cfg.kind == "gmm":
+        idx = np.arange(0, p.means.shape[0], 2)
+        logw = p.logw[idx] - np.log(np.sum(np.exp(p.logw[idx])))
+        return GMMParams(p.means[idx].copy(), p.stds[idx].copy(), _f32(logw))
+    if cfg.kind == "lowrank":
+        r = max(1, p.U.shape[1] // 4)
+        dropped = float(np.sum(p.U[:, r:] ** 2)) / p.U.shape[0]
+        return LowRankGaussianParams(p.mu.copy(), p.U[:, :r].copy(), float(_f32(p.s2 + dropped)))
+    if cfg.kind == "mlp":
+        rng = np.random.default_rng([cfg.seed, 977, p.H])
+        return random_mlp(rng, p.d, max(256, p.H // 4), p.E)
+    raise ValueError(f"no draft model for workload kind {cfg.kind!r}")
+
+
 def make_config(name: str, *, B: Optional[int] = None, d: Optional[int] = None,
                 K: Optional[int] = None, T: Optional[int] = None, seed: int = 0,
                 H: Optional[int] = None, r: Optional[int] = None,
