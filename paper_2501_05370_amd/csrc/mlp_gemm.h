@@ -166,6 +166,11 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   }
 #undef MLPGEMM_FETCH
 
+  // EPI 2, 3: the bias depends on the column only and is read once, ahead of the stores (the fp32
+  // stores of EPI 3 could alias it as far as the compiler knows, which would put a load behind each)
+  float bcol[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bcol[j] = EPI == 1 ? 0.f : p.bias[tile_n * BN + wn * (BN / WN) + j * 32 + l32];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -177,7 +182,7 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
-        const float c = acc[i][j][v] + brow[gn];
+        const float c = acc[i][j][v] + (EPI == 1 ? brow[gn] : bcol[j]);
         if (EPI == 3) p.outf[static_cast<size_t>(src) * p.N + gn] = c;
         else p.outb[static_cast<size_t>(gm) * p.N + gn] = to_bf16_bits(silu(c));
       }

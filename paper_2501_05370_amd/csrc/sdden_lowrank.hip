@@ -12,15 +12,18 @@
 // GEMM 1: P = X Q with the bracket applied per row in the epilogue (each row has its own step k);
 // GEMM 2: out = P' Q^T + g_perp(k) x + (1 - sqrt(ab_k) g_perp(k)) mu.
 //
-// Kernel: 128x128 (second GEMM) or 64x128 (first GEMM) output tile, K-step 16, 4 wavefronts (2x2) of 64x64 = 2x2 v_mfma_f32_32x32x2f32
-// tiles each; A is stored transposed in LDS so both operands are read with unit stride by the
-// 32 lanes of a k-slice; global->register prefetch of the next K-step overlaps the MFMAs.
+// Kernels: for d a multiple of 32 the ring-buffered direct-to-LDS GEMM of lowrank_gemm.h (first
+// product split over K into slabs that a small kernel adds and scales).  Other d fall back to the
+// older kernel below: 128x128 / 64x128 output tile, K-step 16, 4 wavefronts (2x2) of
+// v_mfma_f32_32x32x2f32 tiles, A stored transposed in LDS, global->register prefetch.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <new>
 #include <vector>
 
+#include "lowrank_gemm.h"
 #include "sdden_internal.h"
 #include "sdden_rows.h"
 
@@ -205,6 +208,7 @@ void jacobi_eigen(std::vector<double>& A, std::vector<double>& V, int n) {
 }
 
 struct LowRankDenoiser final : sdden {
+  int eval_ring(int R, const float* X, const int32_t* krow, float* out, hipStream_t st);
   int r = 0, rpad = 0;          // rank, rank padded to a multiple of BK (extra columns are zero)
   float* dev = nullptr;         // all float tables in one allocation
   float *Q = nullptr, *QT = nullptr, *gain = nullptr, *sab = nullptr, *gperp = nullptr, *coef = nullptr,
@@ -213,6 +217,8 @@ struct LowRankDenoiser final : sdden {
   int32_t* rowidx = nullptr;
   int32_t* count = nullptr;
   float* P = nullptr;
+  float* part = nullptr;        // K-split partial sums of the first product
+  int64_t part_rows = 0;
   int cap_rows = 0;
 
   ~LowRankDenoiser() override {
@@ -220,15 +226,23 @@ struct LowRankDenoiser final : sdden {
     if (rowidx) (void)hipFree(rowidx);
     if (count) (void)hipFree(count);
     if (P) (void)hipFree(P);
+    if (part) (void)hipFree(part);
   }
 
   int reserve(int R) override {
     if (R <= cap_rows) return SD_OK;
     if (rowidx) (void)hipFree(rowidx);
     if (P) (void)hipFree(P);
-    rowidx = nullptr; P = nullptr; cap_rows = 0;
+    if (part) (void)hipFree(part);
+    rowidx = nullptr; P = nullptr; part = nullptr; cap_rows = 0; part_rows = 0;
     SD_HIP_TRY(err, hipMalloc(&rowidx, sizeof(int32_t) * static_cast<size_t>(R)));
     SD_HIP_TRY(err, hipMalloc(&P, sizeof(float) * static_cast<size_t>(R) * rpad));
+    if (d % lrgemm::BK == 0) {
+      // the split is chosen per call so that about 1024 workgroups are launched, at most 16 slabs
+      const int64_t rows = std::min<int64_t>(16LL * R, 131072LL + R);
+      SD_HIP_TRY(err, hipMalloc(&part, sizeof(float) * static_cast<size_t>(rows) * rpad));
+      part_rows = rows;
+    }
     if (!count) SD_HIP_TRY(err, hipMalloc(&count, sizeof(int32_t)));
     cap_rows = R;
     return SD_OK;
@@ -240,6 +254,7 @@ struct LowRankDenoiser final : sdden {
       return sdi::fail(err, SD_ERR_WORKSPACE, "sdden_eval(lowrank): %d rows exceed the %d reserved (sdden_reserve)", R, cap_rows);
     hipLaunchKernelGGL(sdrows::compact_rows_kernel, dim3(1), dim3(sdrows::kScan), 0, st, krow, rowidx, count,
                        active, rows_per_chain, R);
+    if (part) return eval_ring(R, X, krow, out, st);
     GemmArgs a;
     a.rowidx = rowidx; a.count = count; a.krow = krow; a.X = X;
     a.gain = gain; a.sab = sab; a.gperp = gperp; a.coef = coef; a.qmu = qmu; a.mu = mu;
@@ -261,6 +276,32 @@ struct LowRankDenoiser final : sdden {
   }
 };
 
+int LowRankDenoiser::eval_ring(int R, const float* X, const int32_t* krow, float* out, hipStream_t st) {
+  // first product: part_s = X[rowidx] Q (K range s), then P' = gain .* (sum_s part_s - sab qmu)
+  const int nk = d / lrgemm::BK;
+  const int tiles = ((R + 127) / 128) * ((rpad + 127) / 128);
+  int nsplit = std::max(1, std::min({16, (1024 + tiles - 1) / tiles, nk / 4}));
+  while (nsplit > 1 && (nk % nsplit != 0 || static_cast<int64_t>(nsplit) * R > part_rows)) --nsplit;
+  lrgemm::Args a{};
+  a.A = X; a.arow = rowidx; a.lda = d; a.Bt = QT; a.ldb = d; a.N = rpad; a.Kdim = d; a.count = count;
+  a.part = part; a.slab_stride = static_cast<int64_t>(R) * rpad;
+  prof.mark(1, st);
+  SD_HIP_TRY(err, (lrgemm::launch<128, 128, 2, 2, 1, 2>(a, R, nsplit, st)));
+  prof.mark(1, st);
+  const int64_t quads = static_cast<int64_t>(R) * (rpad / 4);
+  hipLaunchKernelGGL(lrgemm::reduce_gain_kernel, dim3(static_cast<unsigned>((quads + 255) / 256)), dim3(256), 0, st, part,
+                     a.slab_stride, nsplit, count, rowidx, krow, gain, sab, qmu, P, rpad);
+  // second product: out = P' Q^T + gperp x + coef mu
+  lrgemm::Args b{};
+  b.A = P; b.arow = nullptr; b.lda = rpad; b.Bt = Q; b.ldb = rpad; b.N = d; b.Kdim = rpad; b.count = count;
+  b.rowidx = rowidx; b.krow = krow; b.X = X; b.out = out; b.gperp = gperp; b.coef = coef; b.mu = mu;
+  prof.mark(2, st);
+  SD_HIP_TRY(err, (lrgemm::launch<128, 128, 2, 2, 2, 2>(b, R, 1, st)));
+  prof.mark(2, st);
+  SD_HIP_TRY(err, hipGetLastError());
+  return SD_OK;
+}
+
 }  // namespace
 
 extern "C" int sdden_lowrank_create(int32_t d, int32_t r, const float* mu, const float* U, float s2, int32_t T,
@@ -270,7 +311,7 @@ extern "C" int sdden_lowrank_create(int32_t d, int32_t r, const float* mu, const
     return sdi::fail(E, SD_ERR_ARG, "sdden_lowrank_create: bad argument");
   if (d % BK != 0)
     return sdi::fail(E, SD_ERR_UNSUPPORTED, "sdden_lowrank_create: d=%d must be a multiple of %d", d, BK);
-  const int rpad = ((r + BK - 1) / BK) * BK;
+  const int rpad = ((r + lrgemm::BK - 1) / lrgemm::BK) * lrgemm::BK;     // multiple of both kernels' K-steps
   // Gram matrix G = U^T U (r x r), its eigen-decomposition, and Q = U V diag(lam^-1/2)
   std::vector<double> G(static_cast<size_t>(r) * r, 0.0), V;
   for (int i = 0; i < d; ++i) {
