@@ -300,6 +300,74 @@ def sample(sched, D: Denoiser, B: int, d: int, K: int, seed: int, *, drafter: st
     return out[ids0], st
 
 
+# --------------------------------------------------------------------------------------
+# Efficient frozen drafter (App. "Extending the draft models", paragraph on the efficient frozen
+# draft strategy): the draft mean freezes the target's prediction at the DRAFT state of the
+# window's first position, D(y~_n, n), which the previous window's verification computed, instead
+# of a fresh D(y_n, n).  A window then needs one batched target call, on y_n and all Kt drafts.
+# --------------------------------------------------------------------------------------
+def window_efficient(sched, D: Denoiser, y, n, chain_id, Dfz, K: int, seed: int, *, tau: float = 1.0):
+    """One window with the carried-over frozen prediction ``Dfz`` [B,d].
+
+    Returns (VerifyResult, Ytil, Dq_ext [B,K+1,d], krow_ext [B,K+1], Dfz_next [B,d]):
+    Dq_ext[:, j] = D(state j of the window, n+j) for j = 0 (y_n itself) .. Kt (rows whose step
+    index would be T are not evaluated and stay zero), and Dfz_next = Dq_ext[b, adv[b]], the
+    prediction at the draft state of the position the next window starts from."""
+    y = np.asarray(y, dtype=np.float64)
+    n = np.asarray(n)
+    B, d = y.shape
+    Kt = np.minimum(K, sched.T - n)
+    Ytil, _ = draft_frozen(sched, y, n, chain_id, Dfz, K, seed)
+    # draft means, explicitly: m^p_j = a_k prev + c_k Dfz
+    mp = np.zeros((B, K, d))
+    for j in range(1, K + 1):
+        act = np.nonzero(j <= Kt)[0]
+        if act.size == 0:
+            break
+        k = n[act] + j - 1
+        prev = y[act] if j == 1 else Ytil[act, j - 2]
+        mp[act, j - 1] = sched.a[k, None] * prev + sched.c[k, None] * np.asarray(Dfz, dtype=np.float64)[act]
+    # the one batched target call: the true start state and every draft (also the last one)
+    krow_ext = np.full((B, K + 1), -1, dtype=np.int64)
+    krow_ext[:, 0] = n
+    for j in range(1, K + 1):
+        ok = (j <= Kt) & (n + j < sched.T)
+        krow_ext[ok, j] = n[ok] + j
+    X_ext = np.concatenate([y[:, None, :], Ytil], axis=1)
+    Dq_ext = np.zeros((B, K + 1, d))
+    b_idx, j_idx = np.nonzero(krow_ext >= 0)
+    Dq_ext[b_idx, j_idx] = D(X_ext[b_idx, j_idx], krow_ext[b_idx, j_idx])
+    res = verify(sched, y, n, chain_id, Ytil, Dq_ext[:, :K], K, seed, mp=mp, tau=tau)
+    Dfz_next = Dq_ext[np.arange(B), res.adv]
+    return res, Ytil, Dq_ext, krow_ext, Dfz_next
+
+
+def sample_efficient(sched, D: Denoiser, B: int, d: int, K: int, seed: int, *, tau: float = 1.0,
+                     chain_ids: Optional[np.ndarray] = None):
+    """The whole sampler with the efficient frozen drafter; initialised with D(y_0, 0).
+    Returns (Y_T, stats): stats.target_calls = 1 + number of windows."""
+    ids0 = np.arange(B, dtype=np.int64) if chain_ids is None else np.asarray(chain_ids, dtype=np.int64)
+    ids = ids0.copy()
+    y = philox.initial_state(seed, ids, d)
+    n = np.zeros(ids.shape[0], dtype=np.int64)
+    out = np.zeros((int(ids0.max()) + 1, d))
+    st = SampleStats()
+    Dfz = D(y, n)
+    st.target_calls, st.target_rows = 1, n.size
+    while n.size:
+        res, _, _, krow_ext, Dfz_next = window_efficient(sched, D, y, n, ids, Dfz, K, seed, tau=tau)
+        st.windows += 1
+        st.chain_windows += n.size
+        st.steps += int(res.adv.sum())
+        st.rejections += int(res.rejected.sum())
+        st.target_calls += 1
+        st.target_rows += int((krow_ext >= 0).sum())
+        keep = n + res.adv < sched.T
+        y, n, ids = advance(sched.T, res.y_out, res.adv, n, ids, out)
+        Dfz = Dfz_next[keep]
+    return out[ids0], st
+
+
 def sequential_chain(sched, D: Denoiser, B: int, d: int, seed: int,
                      chain_ids: Optional[np.ndarray] = None, upto: Optional[int] = None):
     """The target chain itself: y_{k+1} = a_k y_k + c_k D(y_k, k) + sigma_k z_{k+1}, with the

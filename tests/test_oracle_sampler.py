@@ -176,3 +176,61 @@ def test_speculative_sampler_is_exact_in_law_and_the_incorrect_one_is_not():
             assert stats.ks_2samp(f(spec), f(seq)).pvalue > 1e-4
     bad, _ = S.sample(sched, den, B, 2, K, seed=303, mechanism="incorrect")
     assert stats.ks_2samp(radius(bad), radius(seq)).pvalue < 1e-12
+
+
+def test_efficient_frozen_reduces_to_the_sequential_chain_when_nothing_is_rejected():
+    """A prediction that does not depend on the state makes draft and target means coincide for any
+    frozen vector, so nothing is rejected: the efficient variant must then return the sequential
+    chain bit for bit with one target call per window plus the initialisation."""
+    sched = W.cosine_schedule(19)
+    const = lambda v, k: np.full_like(np.asarray(v, dtype=np.float64), 0.7)
+    B, K = 30, 4
+    seq = S.sequential_chain(sched, const, B, 3, seed=2)
+    out, st = S.sample_efficient(sched, const, B, 3, K, seed=2)
+    assert np.array_equal(out, seq)
+    assert st.rejections == 0 and st.windows == -(-19 // K)
+    assert st.target_calls == st.windows + 1
+
+
+def test_efficient_frozen_window_structure():
+    sched, den = _ring(T=12)
+    rng = np.random.default_rng(1)
+    B, K, d = 300, 4, 2
+    y = rng.standard_normal((B, d)) * 2
+    n = rng.integers(0, 12, size=B)
+    ids = np.arange(B, dtype=np.int64) + 50
+    Kt = np.minimum(K, 12 - n)
+    # (a) frozen vector = the exact prediction at y_n: identical to the plain frozen window
+    D0 = den(y, n)
+    res, Ytil, Dq_ext, krow_ext, Dnext = S.window_efficient(sched, den, y, n, ids, D0, K, seed=5)
+    ref, Ytil_ref, Dq_ref, _, _, _ = S.window(sched, den, y, n, ids, K, seed=5)
+    assert np.array_equal(Ytil, Ytil_ref) and np.array_equal(res.adv, ref.adv)
+    assert np.allclose(res.y_out, ref.y_out, atol=1e-13) and np.allclose(res.logratio, ref.logratio, atol=1e-12)
+    # rows evaluated: the start state and every draft whose step index is below T
+    for b in range(B):
+        expect = [n[b]] + [n[b] + j if (j <= Kt[b] and n[b] + j < 12) else -1 for j in range(1, K + 1)]
+        assert krow_ext[b].tolist() == expect
+    # the carried prediction is the target's prediction at the draft state of position adv
+    b = int(np.nonzero(ref.rejected & (n + ref.adv < 12))[0][0])
+    j = ref.adv[b]
+    assert np.allclose(Dnext[b], den(Ytil[b:b + 1, j - 1], n[b:b + 1] + j)[0], atol=1e-14)
+    full = np.nonzero(~ref.rejected & (n + ref.adv < 12))[0]
+    assert np.allclose(Dnext[full], den(res.y_out[full], n[full] + res.adv[full]), atol=1e-13)
+    # (b) a stale frozen vector: the first position is no longer accepted for certain
+    stale = D0 + 0.8 * rng.standard_normal((B, d))
+    res2, *_ = S.window_efficient(sched, den, y, n, ids, stale, K, seed=5)
+    assert np.all(res2.logratio[:, 0] != 0) and (res2.adv == 1).sum() > 0 and np.all(res2.adv <= Kt)
+
+
+def test_efficient_frozen_sampler_is_exact_in_law():
+    """Any draft mean gives an exact sampler; with the carried-over prediction the final states must
+    still pass the two-sample tests against the sequential chain."""
+    B, K = 40_000, 6
+    sched, den = _ring()
+    seq = S.sequential_chain(sched, den, B, 2, seed=111)
+    spec, st = S.sample_efficient(sched, den, B, 2, K, seed=222)
+    assert st.steps == B * sched.T and st.target_calls == st.windows + 1
+    assert 0.3 < st.rejections / st.chain_windows < 0.95
+    radius = lambda v: np.linalg.norm(v, axis=1)
+    for f in (lambda v: v[:, 0], lambda v: v[:, 1], radius, lambda v: np.arctan2(v[:, 1], v[:, 0])):
+        assert stats.ks_2samp(f(spec), f(seq)).pvalue > 1e-4
