@@ -87,7 +87,7 @@ def _sampler(cfg, drafter):
     from paper_2501_05370_amd.runner import make_sampler
     if drafter == "independent":
         return make_sampler(cfg, drafter="independent", draft_params=W.draft_params(cfg))
-    return make_sampler(cfg)
+    return make_sampler(cfg, drafter=drafter)
 
 
 def run_gpu(cfg, steps, warmup, stages, drafter="frozen"):
@@ -130,6 +130,11 @@ def run_gpu(cfg, steps, warmup, stages, drafter="frozen"):
         den.sdden_profile_min_rows(0)
     else:
         k_ms, k_launches, _ = timed[plan["stage"]]
+    if drafter == "efficient_frozen" and "den_which" in plan:
+        # one call per window on the start state and all drafts but a chain's final state:
+        # rows = chain-windows + sum Kt - chains finished; expressed through the counters the plan uses
+        counters = list(counters)
+        counters[4] = counters[4] + 2 * counters[1] - cfg.B * steps
     work = plan["work"](counters)
     peak, unit = PEAK[plan["peak"]]
     achieved = work * plan["scale"] / (k_ms * 1e-3) if k_ms > 0 else 0.0
@@ -173,7 +178,8 @@ def run_context(cfg, drafter="frozen"):
         B = int(b.B_active.item())
         windows += 1
     rate = (accepted.double() / reached.clamp(min=1).double()).tolist()
-    calls = windows * (2 if (cfg.kind != "langevin" and K > 1) else 1)
+    calls = windows * (2 if (cfg.kind != "langevin" and K > 1 and drafter != "efficient_frozen") else 1)
+    calls += 1 if drafter == "efficient_frozen" else 0
     out = {"acceptance_rate_by_position": [round(x, 4) for x in rate],
            "target_calls_per_pass": calls, "chain_steps_per_target_call": round(T / calls, 3)}
     del smp
@@ -235,8 +241,13 @@ def cpu_baseline(cfg, budget_s=15.0, drafter="frozen"):
         y = philox.initial_state(seed, ids, cfg.d)
         n = np.zeros(nchains, dtype=np.int64)
         runs += 1
+        Dfz = D(y, n) if drafter == "efficient_frozen" else None
         while n.size and time.perf_counter() - t0 < budget_s:
-            if cfg.kind == "langevin":
+            if drafter == "efficient_frozen":
+                res, _, _, _, Dnext = S.window_efficient(sched, D, y, n, ids, Dfz, cfg.K, seed)
+                y_out, adv = res.y_out, res.adv
+                Dfz = Dnext[n + adv < cfg.T]
+            elif cfg.kind == "langevin":
                 y_out, adv, _, _, _ = L.ula_window(D, y, n, ids, cfg.K, cfg.T, cfg.gamma, seed)
             else:
                 res, *_ = S.window(sched, D, y, n, ids, cfg.K, seed, **kw)
@@ -259,9 +270,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(DESCRIPTIONS))
     ap.add_argument("--stages", action="store_true", help="time every stage (adds event overhead)")
-    ap.add_argument("--drafter", default="frozen", choices=["frozen", "independent"],
-                    help="frozen (default, the benchmark's drafter) or the independent draft model: a cheaper "
-                         "network of the same family called at every window position (c1-c4)")
+    ap.add_argument("--drafter", default="frozen", choices=["frozen", "independent", "efficient_frozen"],
+                    help="frozen (default, the benchmark's drafter); independent: a cheaper network of the same "
+                         "family called at every window position; efficient_frozen: frozen on the prediction "
+                         "carried over from the previous window, one batched target call per window (c1-c4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the untimed extras (acceptance by position, sequential chain on the GPU)")
@@ -283,8 +295,8 @@ def main():
     import workloads as W
     cfg = W.make_config(args.workload)
     steps = args.steps if args.steps is not None else {"c1": 20, "c2": 10, "c3": 3, "c4": 3, "c5": 2}[cfg.name]
-    if args.drafter == "independent" and cfg.kind == "langevin":
-        raise SystemExit("bench.py: the independent drafter is built for the diffusion workloads c1-c4")
+    if args.drafter != "frozen" and cfg.kind == "langevin":
+        raise SystemExit("bench.py: the drafter variants are built for the diffusion workloads c1-c4")
     elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages, args.drafter)
     total_steps = counters[0]
     assert total_steps == cfg.B * cfg.T * steps, (total_steps, cfg.B, cfg.T, steps)

@@ -58,6 +58,11 @@ typedef enum {
 
 #define SD_DRAFT_FROZEN 0         /* draft mean a y~ + c D0, D0 fixed over the window (Sec. 3.1)   */
 #define SD_DRAFT_EXPLICIT 1       /* caller supplies the draft means mp[B,K,d] (any drafter)       */
+#define SD_DRAFT_FROZEN_REUSED 2 /* frozen on a prediction carried over from the previous window:
+                                    D(y~_n, n) at the DRAFT state of position n, which that window's
+                                    verification already computed ("efficient frozen draft strategy",
+                                    App. on extending the draft models).  One batched target call per
+                                    window; window arrays hold K+1 rows per chain, see below.      */
 
 typedef struct sd_ctx sd_ctx;     /* opaque; owns only its device copy of the schedule            */
 
@@ -76,7 +81,20 @@ int sd_create(const sd_schedule* schedule, int32_t d, int32_t K, sd_ctx** out);
 int sd_destroy(sd_ctx* ctx);
 
 int sd_set_seed(sd_ctx* ctx, uint64_t seed);            /* default 0                              */
-int sd_set_draft_mode(sd_ctx* ctx, int mode);           /* SD_DRAFT_FROZEN (default) / _EXPLICIT  */
+int sd_set_draft_mode(sd_ctx* ctx, int mode);           /* SD_DRAFT_FROZEN (default) / _EXPLICIT / _FROZEN_REUSED */
+/* FROZEN_REUSED layout and calls.  The window arrays have K+1 rows per chain:
+ *   X_ext [B,K+1,d]   row 0 = y_n (copied by sd_draft), row j = y~_{n+j}
+ *   krow_ext [B,K+1]  step index of each row the target must evaluate, else -1: row 0 (always), rows
+ *                     1..Kt except a row whose index would be T (the chain's final state)
+ *   Dq_ext [B,K+1,d]  the caller's ONE batched target call on (X_ext, krow_ext) as [B*(K+1), d]
+ * sd_draft(ctx, B, y, n, chain_id, D_frozen, X_ext, krow_ext) freezes the draft mean on D_frozen [B,d];
+ * sd_verify(ctx, B, y, n, chain_id, D_frozen, Dq_ext, X_ext, ...) tests every position including the
+ * first (D_frozen is not the prediction at y_n, so Delta_1 != 0 in general);
+ * sd_advance additionally writes, for every chain that stays in the batch, the next window's frozen
+ * vector D_frozen[new position] = Dq_ext[b][adv[b]] when the two arrays have been registered with
+ * sd_set_carry (both dev, D_frozen must not alias Dq_ext; NULL, NULL unregisters).  The caller
+ * initialises D_frozen with the target's prediction at the initial states. */
+int sd_set_carry(sd_ctx* ctx, const float* Dq_ext, float* D_frozen);
 /* Temperature tau > 0 of the accept test (App. "Influence of the temperature"); 1 = exact.       */
 int sd_set_temperature(sd_ctx* ctx, float tau);
 /* Optional device-resident batch size.  When set (non-NULL, dev int32), every window call treats

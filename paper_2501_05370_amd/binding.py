@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libsd_mi355x.so")
 
 SD_DRAFT_FROZEN = 0
 SD_DRAFT_EXPLICIT = 1
+SD_DRAFT_FROZEN_REUSED = 2
 SD_MAX_WINDOW = 64
 
 
@@ -46,6 +47,7 @@ _SIGNATURES = {
     "sd_draft": (c_int, [c_void_p, c_int32] + [c_void_p] * 7),
     "sd_draft_step": (c_int, [c_void_p, c_int32, c_int32] + [c_void_p] * 10),
     "sd_set_start_prediction": (c_int, [c_void_p, c_void_p]),
+    "sd_set_carry": (c_int, [c_void_p, c_void_p, c_void_p]),
     "sd_verify": (c_int, [c_void_p, c_int32] + [c_void_p] * 12),
     "sd_advance": (c_int, [c_void_p, c_int32] + [c_void_p] * 10),
     "sd_langevin_window": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -167,6 +169,11 @@ class Context:
         ptr = _dev(D_start, torch.float32, "D_start", allow_none=True)
         self._keep_start = D_start
         self._check(self._lib.sd_set_start_prediction(self._h, ptr), "sd_set_start_prediction")
+
+    def sd_set_carry(self, Dq_ext: Optional[torch.Tensor], D_frozen: Optional[torch.Tensor]):
+        self._keep_carry = (Dq_ext, D_frozen)
+        self._check(self._lib.sd_set_carry(self._h, _dev(Dq_ext, torch.float32, "Dq_ext", True),
+                                           _dev(D_frozen, torch.float32, "D_frozen", True)), "sd_set_carry")
 
     def sd_workspace_bytes(self, Bmax: int) -> int:
         return int(self._lib.sd_workspace_bytes(self._h, Bmax))

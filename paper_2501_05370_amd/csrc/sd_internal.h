@@ -18,6 +18,8 @@ struct sd_ctx {
   float* dev_c = nullptr;
   float* dev_sigma = nullptr;
   const int32_t* active = nullptr;
+  const float* carry_src = nullptr;    // FROZEN_REUSED: predictions [B,K+1,d] of the window just verified
+  float* carry_dst = nullptr;          //   and the [B,d] frozen predictions sd_advance fills for the next one
   const float* start_pred = nullptr;   // EXPLICIT mode: D(y_n, n) as [B,d], replaces row 0 of Dq
   void* ws = nullptr;
   size_t ws_bytes = 0;

@@ -88,6 +88,8 @@ struct DraftArgs {
   const float *a, *c, *sigma;
   const int32_t* active;
   int B, d, K, T, nblk;
+  int rs, roff;          // window rows per chain in Ytil / krow and the row the first draft goes to
+                         // (K, 0; or K+1, 1 with row 0 = a copy of y for the one batched target call)
   uint64_t seed;
 };
 
@@ -121,6 +123,17 @@ __global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
       d0[e] = in ? p.D0[row0 + e] : 0.f;
     }
   }
+  if (p.roff) {                         // row 0 of the chain's block: the window-start state itself
+    float* dst = p.Ytil + static_cast<int64_t>(b) * p.rs * p.d + i0;
+    if (VEC == 4) {
+      *reinterpret_cast<float4*>(dst) = make_float4(prev[0], prev[1], prev[2], prev[3]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (i0 + e < p.d) dst[e] = prev[e];
+    }
+    if (blk == 0) p.krow[static_cast<int64_t>(b) * p.rs] = n;
+  }
   for (int j = 0; j < p.K; ++j) {       // position j+1 of the window, produces state n+j+1
     float out[4] = {0.f, 0.f, 0.f, 0.f};
     if (j < Kt) {
@@ -135,7 +148,7 @@ __global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
         out[e] = prev[e];
       }
     }
-    float* dst = p.Ytil + (static_cast<int64_t>(b) * p.K + j) * p.d + i0;
+    float* dst = p.Ytil + (static_cast<int64_t>(b) * p.rs + p.roff + j) * p.d + i0;
     if (VEC == 4) {
       *reinterpret_cast<float4*>(dst) = make_float4(out[0], out[1], out[2], out[3]);
     } else {
@@ -143,7 +156,12 @@ __global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
       for (int e = 0; e < 4; ++e)
         if (i0 + e < p.d) dst[e] = out[e];
     }
-    if (blk == 0) p.krow[static_cast<int64_t>(b) * p.K + j] = (j + 1 <= Kt - 1) ? n + j + 1 : -1;
+    if (blk == 0) {
+      // which drafted states the target must evaluate: all but the last one; with the extra row also the
+      // last one (its prediction is the next window's frozen vector) unless it is the chain's final state
+      const bool need = p.roff ? (j + 1 <= Kt && n + j + 1 < p.T) : (j + 1 <= Kt - 1);
+      p.krow[static_cast<int64_t>(b) * p.rs + p.roff + j] = need ? n + j + 1 : -1;
+    }
   }
 }
 
@@ -242,6 +260,8 @@ __global__ __launch_bounds__(kBlock) void draft_step_kernel(DraftStepArgs p) {
 // ---------------------------------------------------------------------------------------------
 struct VerifyArgs {
   const float *y, *D0mp, *Dq, *Ytil;
+  int rs, roff;                // rows per chain of Ytil / Dq, row of the first draft in Ytil (see DraftArgs)
+  int first_exact;             // FROZEN: D0 is the target's prediction at y, so Delta_1 = 0 and row 0 of Dq is not read
   const float* Dq0;            // EXPLICIT mode, optional: row 0 of Dq kept as a separate [B,d] array
   const int32_t* n;
   const int64_t* id;
@@ -278,7 +298,9 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
   const int64_t id = valid ? p.id[b] : 0;
   const int ncol = p.d / VEC;
   const int64_t rowB = static_cast<int64_t>(b) * p.d;            // offset of y[b], D0[b]
-  const int64_t winB = static_cast<int64_t>(b) * p.K * p.d;      // offset of Ytil[b,0], Dq[b,0]
+  const int64_t winB = static_cast<int64_t>(b) * p.rs * p.d;     // offset of the chain's rows in Ytil, Dq
+  const int64_t yoff = static_cast<int64_t>(p.roff) * p.d;       // first draft within the chain's rows of Ytil
+  const bool skip0 = FROZEN && p.first_exact;
 
   if (t == 0) sh_jr[slot] = -1;
   __syncthreads();
@@ -300,7 +322,7 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
         const int64_t off = static_cast<int64_t>(col) * VEC;
         Pack<VEC> prev, d0;
         if (jc == 0) prev.load(p.y + rowB + off);
-        else prev.load(p.Ytil + winB + static_cast<int64_t>(jc - 1) * p.d + off);
+        else prev.load(p.Ytil + winB + yoff + static_cast<int64_t>(jc - 1) * p.d + off);
         if (FROZEN) d0.load(p.D0mp + rowB + off);
 #pragma unroll
         for (int jj = 0; jj < kJC; ++jj) {
@@ -308,9 +330,9 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
           if (j < Kt) {
             const int64_t r = winB + static_cast<int64_t>(j) * p.d + off;
             Pack<VEC> cur, dq, mp;
-            cur.load(p.Ytil + r);
+            cur.load(p.Ytil + r + yoff);
             if (FROZEN) {
-              if (j > 0) dq.load(p.Dq + r);
+              if (j > 0 || !skip0) dq.load(p.Dq + r);
             } else {
               if (j == 0 && p.Dq0) dq.load(p.Dq0 + rowB + off);
               else dq.load(p.Dq + r);
@@ -322,7 +344,7 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
               if (FROZEN) {
                 w = static_cast<double>(cur.v[e]) - static_cast<double>(ak[jj]) * prev.v[e] -
                     static_cast<double>(ck[jj]) * d0.v[e];
-                dl = (j > 0) ? static_cast<double>(d0.v[e]) - static_cast<double>(dq.v[e]) : 0.0;
+                dl = (j > 0 || !skip0) ? static_cast<double>(d0.v[e]) - static_cast<double>(dq.v[e]) : 0.0;
               } else {
                 w = static_cast<double>(cur.v[e]) - static_cast<double>(mp.v[e]);
                 dl = static_cast<double>(mp.v[e]) - (static_cast<double>(ak[jj]) * prev.v[e] +
@@ -418,7 +440,7 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
   }
   float* dst = p.y_out + rowB;
   if (jr < 0) {
-    const float* src = Kt > 0 ? p.Ytil + winB + static_cast<int64_t>(Kt - 1) * p.d : p.y + rowB;
+    const float* src = Kt > 0 ? p.Ytil + winB + yoff + static_cast<int64_t>(Kt - 1) * p.d : p.y + rowB;
     for (int col = t; col < ncol; col += TPC) {
       Pack<VEC> v;
       v.load(src + static_cast<int64_t>(col) * VEC);
@@ -429,13 +451,13 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
   const int k = n + jr;
   const double a = p.a[k], c = p.c[k];
   const double two_coef = 2.0 * sh_coef[slot];
-  const float* prevrow = jr == 0 ? p.y + rowB : p.Ytil + winB + static_cast<int64_t>(jr - 1) * p.d;
+  const float* prevrow = jr == 0 ? p.y + rowB : p.Ytil + winB + yoff + static_cast<int64_t>(jr - 1) * p.d;
   const int64_t r = winB + static_cast<int64_t>(jr) * p.d;
   for (int col = t; col < ncol; col += TPC) {
     const int64_t off = static_cast<int64_t>(col) * VEC;
     Pack<VEC> prev, cur, dq, x, o;
     prev.load(prevrow + off);
-    cur.load(p.Ytil + r + off);
+    cur.load(p.Ytil + r + yoff + off);
     if (!FROZEN && jr == 0 && p.Dq0) dq.load(p.Dq0 + rowB + off);
     else dq.load(p.Dq + r + off);
     if (FROZEN) x.load(p.D0mp + rowB + off);
@@ -533,7 +555,10 @@ __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __res
                                                               const int64_t* __restrict__ outrow,
                                                               float* __restrict__ y,
                                                               float* __restrict__ out, int Bprev,
-                                                              int d, int chunks) {
+                                                              int d, int chunks,
+                                                              const float* __restrict__ carry_src,
+                                                              float* __restrict__ carry_dst,
+                                                              const int32_t* __restrict__ adv, int rs) {
   // Bprev = number of chains that entered the window (host bound; rows beyond the device-side
   // count carry dest = -2 from the fill below and are skipped).
   const int b = blockIdx.x / chunks;
@@ -549,6 +574,12 @@ __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __res
     Pack<VEC> v;
     v.load(src + static_cast<int64_t>(col) * VEC);
     v.store(dst + static_cast<int64_t>(col) * VEC);
+    if (carry_src && dpos >= 0) {
+      // the surviving chain also takes along the target's prediction at the draft state of the
+      // position it advanced to: next window's frozen vector
+      v.load(carry_src + (static_cast<int64_t>(b) * rs + adv[b]) * d + static_cast<int64_t>(col) * VEC);
+      v.store(carry_dst + static_cast<int64_t>(dpos) * d + static_cast<int64_t>(col) * VEC);
+    }
   }
 }
 
@@ -621,7 +652,7 @@ int sd_set_seed(sd_ctx* ctx, uint64_t seed) {
 
 int sd_set_draft_mode(sd_ctx* ctx, int mode) {
   if (!ctx) return SD_ERR_ARG;
-  if (mode != SD_DRAFT_FROZEN && mode != SD_DRAFT_EXPLICIT)
+  if (mode != SD_DRAFT_FROZEN && mode != SD_DRAFT_EXPLICIT && mode != SD_DRAFT_FROZEN_REUSED)
     return sdi::fail(ctx->err, SD_ERR_ARG, "sd_set_draft_mode: unknown mode %d", mode);
   ctx->mode = mode;
   return SD_OK;
@@ -633,6 +664,15 @@ int sd_set_temperature(sd_ctx* ctx, float tau) {
     return sdi::fail(ctx->err, SD_ERR_ARG, "sd_set_temperature: tau=%g must be finite and > 0",
                      static_cast<double>(tau));
   ctx->tau = tau;
+  return SD_OK;
+}
+
+int sd_set_carry(sd_ctx* ctx, const float* Dq_ext, float* D_frozen) {
+  if (!ctx) return SD_ERR_ARG;
+  if ((Dq_ext == nullptr) != (D_frozen == nullptr))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_set_carry: give both arrays or neither");
+  ctx->carry_src = Dq_ext;
+  ctx->carry_dst = D_frozen;
   return SD_OK;
 }
 
@@ -682,9 +722,9 @@ int sd_init_state(sd_ctx* ctx, int32_t B, const int64_t* chain_id, float* y, int
 int sd_draft(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int64_t* chain_id,
              const float* D0, float* Ytilde, int32_t* krow, void* stream) {
   if (int rc = check_ctx(ctx)) return rc;
-  if (ctx->mode != SD_DRAFT_FROZEN)
-    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_draft: only the frozen drafter is rolled out by the library; "
-                                           "in EXPLICIT mode the caller produces the drafts and their means");
+  if (ctx->mode == SD_DRAFT_EXPLICIT)
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_draft: only the frozen drafters are rolled out in one call; "
+                                           "in EXPLICIT mode the caller produces the drafts and their means (sd_draft_step)");
   if (B < 0 || (B > 0 && (!y || !n || !chain_id || !D0 || !Ytilde || !krow)))
     return sdi::fail(ctx->err, SD_ERR_ARG, "sd_draft: bad argument");
   if (B == 0) return SD_OK;
@@ -692,6 +732,8 @@ int sd_draft(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int
   p.y = y; p.D0 = D0; p.n = n; p.id = chain_id; p.Ytil = Ytilde; p.krow = krow;
   p.a = ctx->dev_a; p.c = ctx->dev_c; p.sigma = ctx->dev_sigma; p.active = ctx->active;
   p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.nblk = (ctx->d + 3) / 4; p.seed = ctx->seed;
+  const bool ext = ctx->mode == SD_DRAFT_FROZEN_REUSED;
+  p.rs = ext ? ctx->K + 1 : ctx->K; p.roff = ext ? 1 : 0;
   const int64_t total = static_cast<int64_t>(B) * p.nblk;
   const int64_t grid = (total + kBlock - 1) / kBlock;
   if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_draft: B*d too large");
@@ -740,9 +782,11 @@ int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const in
   p.y = y; p.D0mp = D0_or_mp; p.Dq = Dq; p.Ytil = Ytilde; p.n = n; p.id = chain_id;
   p.y_out = y_out; p.adv = adv; p.rej = rejected; p.logratio = logratio; p.logu = logu;
   p.Dq0 = ctx->mode == SD_DRAFT_EXPLICIT ? ctx->start_pred : nullptr;
+  const bool ext = ctx->mode == SD_DRAFT_FROZEN_REUSED;
+  p.rs = ext ? ctx->K + 1 : ctx->K; p.roff = ext ? 1 : 0; p.first_exact = ctx->mode == SD_DRAFT_FROZEN;
   p.a = ctx->dev_a; p.c = ctx->dev_c; p.sigma = ctx->dev_sigma; p.active = ctx->active;
   p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.seed = ctx->seed; p.inv_tau = 1.0 / ctx->tau;
-  const bool frozen = ctx->mode == SD_DRAFT_FROZEN;
+  const bool frozen = ctx->mode != SD_DRAFT_EXPLICIT;
   const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y) && sdi::aligned16(D0_or_mp) && sdi::aligned16(p.Dq0) &&
                    sdi::aligned16(Dq) && sdi::aligned16(Ytilde) && sdi::aligned16(y_out);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -778,15 +822,17 @@ int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, c
   hipLaunchKernelGGL(advance_scan_kernel, dim3(1), dim3(kScanBlock), 0, st, adv, rejected, n, chain_id,
                      dest, outrow, B_active, counters, ctx->active, B, ctx->T, ctx->K);
   if (B > 0) {
-    const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y_out) && sdi::aligned16(y) && sdi::aligned16(out);
+    const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y_out) && sdi::aligned16(y) && sdi::aligned16(out) &&
+                     sdi::aligned16(ctx->carry_src) && sdi::aligned16(ctx->carry_dst);
     const int ncol = vec ? ctx->d / 4 : ctx->d;
     const int chunks = (ncol + kBlock - 1) / kBlock;
     const int64_t grid = static_cast<int64_t>(B) * chunks;
     if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_advance: B*d too large");
+    const float* csrc = ctx->mode == SD_DRAFT_FROZEN_REUSED ? ctx->carry_src : nullptr;
     if (vec) hipLaunchKernelGGL(advance_move_kernel<4>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
-                                y_out, dest, outrow, y, out, B, ctx->d, chunks);
+                                y_out, dest, outrow, y, out, B, ctx->d, chunks, csrc, ctx->carry_dst, adv, ctx->K + 1);
     else     hipLaunchKernelGGL(advance_move_kernel<1>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
-                                y_out, dest, outrow, y, out, B, ctx->d, chunks);
+                                y_out, dest, outrow, y, out, B, ctx->d, chunks, csrc, ctx->carry_dst, adv, ctx->K + 1);
   }
   SD_HIP_TRY(ctx->err, hipGetLastError());
   return SD_OK;

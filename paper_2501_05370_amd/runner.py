@@ -4,7 +4,7 @@ from __future__ import annotations
 import torch
 
 from .binding import Context, Denoiser
-from .sampler import DiffusionSampler, IndependentDrafterSampler, LangevinSampler
+from .sampler import DiffusionSampler, EfficientFrozenSampler, IndependentDrafterSampler, LangevinSampler
 
 
 def make_context(cfg, seed=None) -> Context:
@@ -38,6 +38,10 @@ def make_sampler(cfg, B=None, out_rows=None, seed=None, drafter: str = "frozen",
         den = make_denoiser(cfg, B * cfg.K)
         draft = make_denoiser(cfg, B, draft_params)
         return IndependentDrafterSampler(ctx, den, draft, B, out_rows)
+    if drafter == "efficient_frozen":
+        if cfg.kind == "langevin":
+            raise ValueError("the efficient frozen drafter needs a diffusion workload")
+        return EfficientFrozenSampler(ctx, make_denoiser(cfg, B * (cfg.K + 1)), B, out_rows)
     if drafter != "frozen":
         raise ValueError(drafter)
     if cfg.kind == "langevin":

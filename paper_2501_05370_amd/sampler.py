@@ -167,6 +167,40 @@ class IndependentDrafterSampler(_SamplerBase):
             ctx.sd_verify(B, b.y, b.n, b.chain_id, b.mp, b.Dq, b.Ytilde, b.y_out, b.adv, b.rejected, lr, lu)
 
 
+class EfficientFrozenSampler(_SamplerBase):
+    """The efficient frozen drafter: the draft mean freezes the target's prediction at the previous
+    window's draft state, carried through ``sd_advance``; one batched target call per window on the
+    start state and all drafts (``sd_draft`` -> ``sdden_eval`` -> ``sd_verify`` -> ``sd_advance``)."""
+
+    def __init__(self, ctx: Context, den: Denoiser, B: int, out_rows: Optional[int] = None):
+        from .binding import SD_DRAFT_FROZEN_REUSED
+        self.den = den
+        self._setup(ctx, B, out_rows, False)
+        b, K, d, f32 = self.buf, ctx.K, ctx.d, dict(dtype=torch.float32, device="cuda")
+        b.Dfz = torch.zeros(B, d, **f32)
+        b.X_ext = torch.zeros(B, K + 1, d, **f32)
+        b.krow_ext = torch.full((B, K + 1), -1, dtype=torch.int32, device="cuda")
+        b.Dq_ext = torch.zeros(B, K + 1, d, **f32)
+        ctx.sd_set_draft_mode(SD_DRAFT_FROZEN_REUSED)
+        ctx.sd_set_carry(b.Dq_ext, b.Dfz)
+
+    def start(self, chain_ids: torch.Tensor, reset_counters: bool = True) -> int:
+        B = super().start(chain_ids, reset_counters)
+        b = self.buf
+        self.den.sdden_eval(B, b.y, b.n, b.Dfz)                 # initialisation: D(y_0, 0)
+        return B
+
+    def window(self, B: int, diagnostics=None):
+        b, ctx, d, K, t = self.buf, self.ctx, self.ctx.d, self.ctx.K, self.timer
+        with t.stage("draft", B):
+            ctx.sd_draft(B, b.y, b.n, b.chain_id, b.Dfz, b.X_ext, b.krow_ext)
+        with t.stage("predict_drafts", B):
+            self.den.sdden_eval(B * (K + 1), b.X_ext.view(-1, d), b.krow_ext.view(-1), b.Dq_ext.view(-1, d))
+        lr, lu = diagnostics if diagnostics is not None else (None, None)
+        with t.stage("verify", B):
+            ctx.sd_verify(B, b.y, b.n, b.chain_id, b.Dfz, b.Dq_ext, b.X_ext, b.y_out, b.adv, b.rejected, lr, lu)
+
+
 class LangevinSampler(_SamplerBase):
     def __init__(self, ctx: Context, means: torch.Tensor, logw: torch.Tensor, comp_std: float,
                  gamma: float, B: int, out_rows: Optional[int] = None):
