@@ -28,6 +28,37 @@ from . import philox
 Grad = Callable[[np.ndarray], np.ndarray]
 
 
+class Phi4Energy:
+    """The phi^4 lattice energy of the Langevin appendix on an L x L grid,
+        E(x) = (beta/2) sum_{|i-j|=1} (x_i - x_j)^2 + sum_i (x_i^2 - 1)^2.
+    Reading (the text fixes neither): the neighbour sum runs over ORDERED pairs, so every bond of the
+    grid counts twice, and the grid is periodic.  Of the four combinations (ordered / unordered
+    pairs, periodic / free boundary) this is the one whose plain ULA run (step 1e-3, 1e5 iterations,
+    beta = 100, 8 x 8) reproduces the mean energy printed in the table of that appendix (62.27);
+    the others give about 41, 40 and 56.
+        grad E_i = 2 beta (4 x_i - sum of the four neighbours) + 4 x_i (x_i^2 - 1).
+    Sites are numbered row by row, i = row * L + col."""
+
+    def __init__(self, L: int, beta: float):
+        assert L >= 3, "with L < 3 the four neighbours of a site are not distinct"
+        self.L, self.beta = int(L), float(beta)
+
+    def _grid(self, x):
+        x = np.asarray(x, dtype=np.float64)
+        return x.reshape(x.shape[0], self.L, self.L)
+
+    def energy(self, x) -> np.ndarray:
+        X = self._grid(x)
+        bonds = np.sum((X - np.roll(X, 1, axis=1)) ** 2, axis=(1, 2)) + np.sum((X - np.roll(X, 1, axis=2)) ** 2, axis=(1, 2))
+        return self.beta * bonds + np.sum((X * X - 1.0) ** 2, axis=(1, 2))
+
+    def __call__(self, x, k=None) -> np.ndarray:
+        X = self._grid(x)
+        nb = np.roll(X, 1, axis=1) + np.roll(X, -1, axis=1) + np.roll(X, 1, axis=2) + np.roll(X, -1, axis=2)
+        g = 2.0 * self.beta * (4.0 * X - nb) + 4.0 * X * (X * X - 1.0)
+        return g.reshape(np.asarray(x).shape)
+
+
 def ula_window(gradE: Grad, x, n, chain_id, K: int, T: int, gamma: float, seed: int,
                grad_proxy: Optional[Grad] = None):
     """One window for every chain.  Returns (x_out [B,d], adv [B], rejected [B],
