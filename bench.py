@@ -37,6 +37,7 @@ DESCRIPTIONS = {
     "c3": "c3: linear-Gaussian DDPM d=3072, 2048 chains, rank-256 Woodbury denoiser (fp32 MFMA), cosine T=250, K=10",
     "c4": "c4: MLP DDPM d=12288, 512 chains, 3-layer width-4096 SiLU MLP (bf16 MFMA), linear T=500, K=16",
     "c5": "c5: speculative ULA d=1000, 16384 chains, 16-component GMM score, gamma=1e-2, T=2000, K=16",
+    "phi4": "phi4: speculative ULA on the phi^4 lattice energy, 8x8 periodic grid, beta=100, gamma=1e-3, 16384 chains, T=2000, K=20",
 }
 
 # HBM bytes per launch of the roofline kernel (fetched * 2.0 + written * 1.0 of the rocprofv3 FETCH_SIZE /
@@ -79,6 +80,13 @@ def roofline_plan(cfg):
         return dict(kernel="langevin_window_wave_kernel<4> (fused draft + score + verify, one wavefront per chain)", stage="langevin_window",
                     bound="alu", peak="alu_fp64", scale=1e-12,
                     work=lambda c: float(c[0] + c[1]) * d * (5.0 * M + 14.0))
+    if cfg.kind == "phi4":
+        # lane operations per site and evaluated position: Philox + Box-Muller about 40 (int32 / fp32), the
+        # stencil gradient, Delta, the two dot products and the update about 30 in fp64 (counted twice:
+        # half-rate), against the fp32 vector peak
+        return dict(kernel="phi4_window_kernel<16> (fused draft + stencil gradient + verify, 16 lanes per chain)",
+                    stage="langevin_window", bound="alu", peak="alu_fp32", scale=1e-12,
+                    work=lambda c: float(c[0] + c[1]) * d * 100.0)
     raise ValueError(cfg.kind)
 
 
@@ -178,7 +186,7 @@ def run_context(cfg, drafter="frozen"):
         B = int(b.B_active.item())
         windows += 1
     rate = (accepted.double() / reached.clamp(min=1).double()).tolist()
-    calls = windows * (2 if (cfg.kind != "langevin" and K > 1 and drafter != "efficient_frozen") else 1)
+    calls = windows * (2 if (cfg.kind not in ("langevin", "phi4") and K > 1 and drafter != "efficient_frozen") else 1)
     calls += 1 if drafter == "efficient_frozen" else 0
     out = {"acceptance_rate_by_position": [round(x, 4) for x in rate],
            "target_calls_per_pass": calls, "chain_steps_per_target_call": round(T / calls, 3)}
@@ -212,7 +220,7 @@ def cpu_baseline(cfg, budget_s=15.0, drafter="frozen"):
         blas_threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
     except Exception:
         blas_threads = 1
-    nchains = {"c1": 64, "c2": 256, "c3": 16, "c4": 4, "c5": 16}[cfg.name]
+    nchains = {"c1": 64, "c2": 256, "c3": 16, "c4": 4, "c5": 16, "phi4": 256}[cfg.name]
     nchains = min(nchains, cfg.B)
     ids = np.arange(nchains, dtype=np.int64)
     sched = cfg.schedule
@@ -222,6 +230,8 @@ def cpu_baseline(cfg, budget_s=15.0, drafter="frozen"):
         D, cores = LowRankDenoiser(cfg.params, sched.alpha_bar_state), blas_threads
     elif cfg.kind == "mlp":
         D, cores = MLPDenoiser(cfg.params), blas_threads
+    elif cfg.kind == "phi4":
+        D, cores = L.Phi4Energy(cfg.params.L, cfg.params.beta), 1
     else:
         D, cores = GMMScore(cfg.params), 1
     kw = {}
@@ -247,7 +257,7 @@ def cpu_baseline(cfg, budget_s=15.0, drafter="frozen"):
                 res, _, _, _, Dnext = S.window_efficient(sched, D, y, n, ids, Dfz, cfg.K, seed)
                 y_out, adv = res.y_out, res.adv
                 Dfz = Dnext[n + adv < cfg.T]
-            elif cfg.kind == "langevin":
+            elif cfg.kind in ("langevin", "phi4"):
                 y_out, adv, _, _, _ = L.ula_window(D, y, n, ids, cfg.K, cfg.T, cfg.gamma, seed)
             else:
                 res, *_ = S.window(sched, D, y, n, ids, cfg.K, seed, **kw)
@@ -294,8 +304,8 @@ def main():
                          "chain id with no collective on the hot path); run with --gpus 1")
     import workloads as W
     cfg = W.make_config(args.workload)
-    steps = args.steps if args.steps is not None else {"c1": 20, "c2": 10, "c3": 3, "c4": 3, "c5": 2}[cfg.name]
-    if args.drafter != "frozen" and cfg.kind == "langevin":
+    steps = args.steps if args.steps is not None else {"c1": 20, "c2": 10, "c3": 3, "c4": 3, "c5": 2, "phi4": 3}[cfg.name]
+    if args.drafter != "frozen" and cfg.kind in ("langevin", "phi4"):
         raise SystemExit("bench.py: the drafter variants are built for the diffusion workloads c1-c4")
     elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages, args.drafter)
     total_steps = counters[0]
@@ -307,7 +317,7 @@ def main():
         "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": round(1e3 * elapsed / steps, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.kind == "mlp" else "f32", "data": "synthetic",
+        "dtype": "bf16" if cfg.kind == "mlp" else ("f64" if cfg.kind in ("langevin", "phi4") else "f32"), "data": "synthetic",
         "config": {"workload": DESCRIPTIONS[cfg.name], "chains": cfg.B, "d": cfg.d, "window_K": cfg.K,
                    "chain_steps_T": cfg.T, "drafter": args.drafter, "seed": cfg.seed,
                    "step_definition": "one full sampler pass: all chains from step 0 to T"},

@@ -183,6 +183,17 @@ int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
                        float comp_std, int32_t M, float gamma, float* x_out, int32_t* adv,
                        uint8_t* rejected, float* logratio, float* logu, void* stream);
 
+/* The same window for the phi^4 lattice energy of the Langevin appendix (table of sampling metrics)
+ * on an L x L periodic grid, sites numbered row by row, d = L*L (3 <= L <= 16):
+ *   E(x) = (beta/2) sum over ordered neighbour pairs (x_i - x_j)^2 + sum_i (x_i^2 - 1)^2
+ *        = beta sum over bonds (x_i - x_j)^2 + sum_i (x_i^2 - 1)^2   (every bond counts twice),
+ *   grad E_i = 2 beta (4 x_i - its four neighbours) + 4 x_i (x_i^2 - 1).
+ * Arguments as in sd_langevin_window with (L, beta) in place of the mixture. */
+int sd_langevin_window_phi4(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
+                            const int64_t* chain_id, int32_t L, float beta, float gamma,
+                            float* x_out, int32_t* adv, uint8_t* rejected, float* logratio,
+                            float* logu, void* stream);
+
 /* Text of the last error on this context (or of the last failed sd_create when ctx is NULL). */
 const char* sd_last_error(const sd_ctx* ctx);
 

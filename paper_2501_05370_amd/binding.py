@@ -52,6 +52,8 @@ _SIGNATURES = {
     "sd_advance": (c_int, [c_void_p, c_int32] + [c_void_p] * 10),
     "sd_langevin_window": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                    c_float, c_int32, c_float] + [c_void_p] * 6),
+    "sd_langevin_window_phi4": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int32, c_float, c_float]
+                                + [c_void_p] * 6),
     "sd_last_error": (c_char_p, [c_void_p]),
     # sdden.h
     "sdden_gmm_create": (c_int, [c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_int32, c_void_p,
@@ -235,6 +237,15 @@ class Context:
             _dev(adv, torch.int32, "adv"), _dev(rejected, torch.uint8, "rejected", True),
             _dev(logratio, torch.float32, "logratio", True), _dev(logu, torch.float32, "logu", True),
             _stream()), "sd_langevin_window")
+
+    def sd_langevin_window_phi4(self, B, x, n, chain_id, L, beta, gamma, x_out, adv, rejected=None,
+                                logratio=None, logu=None):
+        self._check(self._lib.sd_langevin_window_phi4(
+            self._h, B, _dev(x, torch.float32, "x"), _dev(n, torch.int32, "n"),
+            _dev(chain_id, torch.int64, "chain_id"), L, beta, gamma, _dev(x_out, torch.float32, "x_out"),
+            _dev(adv, torch.int32, "adv"), _dev(rejected, torch.uint8, "rejected", True),
+            _dev(logratio, torch.float32, "logratio", True), _dev(logu, torch.float32, "logu", True),
+            _stream()), "sd_langevin_window_phi4")
 
 
 class Denoiser:

@@ -467,6 +467,165 @@ hipError_t launch_wave(const LangevinArgs& p, int dpad, hipStream_t st) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// phi^4 lattice energy on an L x L periodic grid (Langevin appendix, table of sampling metrics):
+//   E(x) = (beta/2) sum over ordered neighbour pairs (x_i - x_j)^2 + sum_i (x_i^2 - 1)^2,
+//   grad E_i = 2 beta (4 x_i - four neighbours) + 4 x_i (x_i^2 - 1).
+// G lanes work on one chain (G = power of two >= d/4, one Philox block of four sites per lane),
+// 64/G chains share a wavefront and 256/G a workgroup.  The chain's state is mirrored in a
+// wavefront-private slice of LDS for the neighbour reads; no workgroup barrier is used, since the
+// chains of a workgroup leave their walks at different positions.  A wavefront walks until none
+// of its chains is alive; a chain that has rejected or finished is masked.
+// ---------------------------------------------------------------------------------------------
+struct Phi4Args {
+  const float* x;
+  const int32_t* n;
+  const int64_t* id;
+  float* x_out;
+  int32_t* adv;
+  uint8_t* rej;
+  float *logratio, *logu;
+  const int32_t* active;
+  int B, d, L, K, T;
+  uint64_t seed;
+  double gamma, beta, inv_tau;
+};
+
+template <int G>
+__device__ __forceinline__ double group_sum_f64(double v) {
+#pragma unroll
+  for (int s = G / 2; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+  return v;
+}
+
+template <int G>
+__global__ __launch_bounds__(256) void phi4_window_kernel(Phi4Args p) {
+  constexpr int CPWV = 64 / G;                       // chains per wavefront
+  extern __shared__ __align__(16) double sh_x[];     // [256 / G][d]
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int sub = lane / G, gl = lane % G;
+  const int slot = wave * CPWV + sub;
+  const int Bact = p.active ? min(p.B, max(0, *p.active)) : p.B;
+  const int b_raw = blockIdx.x * (4 * CPWV) + slot;
+  const bool valid = b_raw < Bact;
+  const int b = valid ? b_raw : 0;
+  const int d = p.d, L = p.L;
+  const int n = valid ? p.n[b] : 0;
+  const int Kt = valid ? max(0, min(p.K, p.T - n)) : 0;
+  const int64_t id = valid ? p.id[b] : 0;
+  const double gamma = p.gamma, beta2 = 2.0 * p.beta;
+  const double sq2g = sqrt(2.0 * gamma), sqg2 = sqrt(0.5 * gamma);
+  double* xs = sh_x + static_cast<size_t>(slot) * d;
+
+  bool own[4];
+  int nb[4][4];
+  double cur[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int s = 4 * gl + e;
+    own[e] = s < d;
+    const int sc = own[e] ? s : 0;
+    const int r = sc / L, c = sc % L;
+    nb[e][0] = ((r + L - 1) % L) * L + c;
+    nb[e][1] = ((r + 1) % L) * L + c;
+    nb[e][2] = r * L + (c + L - 1) % L;
+    nb[e][3] = r * L + (c + 1) % L;
+    cur[e] = (valid && own[e]) ? static_cast<double>(p.x[static_cast<int64_t>(b) * d + s]) : 0.0;
+  }
+
+  // grad E at `cur`: mirror the state in LDS, then read the four neighbours.  Writers and readers
+  // are lanes of one wavefront and the two accesses are separate instructions in program order.
+  auto gradient = [&](double g[4]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (own[e]) xs[4 * gl + e] = cur[e];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      double v = 0.0;
+      if (own[e]) {
+        const double s4 = xs[nb[e][0]] + xs[nb[e][1]] + xs[nb[e][2]] + xs[nb[e][3]];
+        v = beta2 * (4.0 * cur[e] - s4) + 4.0 * cur[e] * (cur[e] * cur[e] - 1.0);
+      }
+      g[e] = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();                 // reads done before the next mirror overwrites
+  };
+
+  double g0[4];
+  gradient(g0);
+
+  int jr = -1;
+  for (int j = 0; j < p.K; ++j) {
+    const bool alive = valid && j < Kt && jr < 0;
+    if (__ballot(alive) == 0ull) break;              // uniform over the wavefront
+    const uint32_t k1 = static_cast<uint32_t>(n + j + 1);
+    float z[4];
+    sdrng::normal4(p.seed, id, k1, sdrng::kStreamNoise, static_cast<uint32_t>(gl), z);
+    const double lu = sdrng::log_uniform(p.seed, id, k1);
+    double lr = 0.0, coef = 0.0;
+    bool reject = false;
+    double dl[4] = {0.0, 0.0, 0.0, 0.0};
+    if (j > 0) {                                     // position 1: the target gradient IS g0
+      gradient(dl);                                  // every lane of the wavefront takes part
+      double a1 = 0.0, a2 = 0.0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        dl[e] = (own[e] && alive) ? sqg2 * (dl[e] - g0[e]) : 0.0;
+        a1 = fma(static_cast<double>(z[e]), dl[e], a1);
+        a2 = fma(dl[e], dl[e], a2);
+      }
+      const double S1 = group_sum_f64<G>(a1), S2 = group_sum_f64<G>(a2);
+      lr = (-S1 - 0.5 * S2) * p.inv_tau;
+      reject = alive && !(S2 == 0.0 || lu <= fmin(0.0, lr));
+      coef = S2 > 0.0 ? S1 / S2 : 0.0;
+    }
+    if (alive && gl == 0) {
+      if (p.logratio) p.logratio[static_cast<int64_t>(b) * p.K + j] = static_cast<float>(lr);
+      if (p.logu) p.logu[static_cast<int64_t>(b) * p.K + j] = static_cast<float>(lu);
+    }
+    if (alive) {
+      if (reject) {
+        jr = j;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (own[e])                                // target gradient = g0 + Delta / sqrt(gamma/2)
+            cur[e] = cur[e] - gamma * (g0[e] + dl[e] / sqg2) + sq2g * (static_cast<double>(z[e]) - 2.0 * coef * dl[e]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (own[e]) cur[e] = cur[e] - gamma * g0[e] + sq2g * static_cast<double>(z[e]);
+      }
+    }
+  }
+
+  if (!valid) return;
+  const int jdone = jr >= 0 ? jr + 1 : Kt;
+  if (gl == 0) {
+    p.adv[b] = jdone;
+    if (p.rej) p.rej[b] = jr >= 0 ? 1 : 0;
+    for (int j = jdone; j < p.K; ++j) {
+      if (p.logratio) p.logratio[static_cast<int64_t>(b) * p.K + j] = 0.f;
+      if (p.logu) p.logu[static_cast<int64_t>(b) * p.K + j] = 0.f;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (own[e]) p.x_out[static_cast<int64_t>(b) * d + 4 * gl + e] = static_cast<float>(cur[e]);
+}
+
+template <int G>
+hipError_t launch_phi4(const Phi4Args& p, hipStream_t st) {
+  constexpr int chains_per_wg = 256 / G;
+  const size_t shmem = sizeof(double) * static_cast<size_t>(chains_per_wg) * p.d;
+  const unsigned grid = static_cast<unsigned>((p.B + chains_per_wg - 1) / chains_per_wg);
+  hipLaunchKernelGGL(phi4_window_kernel<G>, dim3(grid), dim3(256), shmem, st, p);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 extern "C" int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
@@ -510,5 +669,32 @@ extern "C" int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const 
     default: hipLaunchKernelGGL((langevin_window_kernel<4, 16>), grid, block, 0, st, p); break;
   }
   SD_HIP_TRY(ctx->err, hipGetLastError());
+  return SD_OK;
+}
+
+extern "C" int sd_langevin_window_phi4(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
+                                       const int64_t* chain_id, int32_t L, float beta, float gamma, float* x_out,
+                                       int32_t* adv, uint8_t* rejected, float* logratio, float* logu, void* stream) {
+  if (!ctx) return SD_ERR_ARG;
+  if (B < 0 || L < 3 || !(beta >= 0.f) || !(gamma > 0.f) || (B > 0 && (!x || !n || !chain_id || !x_out || !adv)))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_langevin_window_phi4: bad argument (L >= 3, beta >= 0, gamma > 0)");
+  if (L * L != ctx->d)
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_langevin_window_phi4: the context's d=%d is not L*L=%d", ctx->d, L * L);
+  if (ctx->d > 256)
+    return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_langevin_window_phi4: grids up to 16 x 16 (d=%d)", ctx->d);
+  if (B == 0) return SD_OK;
+  Phi4Args p;
+  p.x = x; p.n = n; p.id = chain_id; p.x_out = x_out; p.adv = adv; p.rej = rejected; p.logratio = logratio; p.logu = logu;
+  p.active = ctx->active; p.B = B; p.d = ctx->d; p.L = L; p.K = ctx->K; p.T = ctx->T; p.seed = ctx->seed;
+  p.gamma = gamma; p.beta = beta; p.inv_tau = 1.0 / ctx->tau;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int groups = (ctx->d + 3) / 4;
+  hipError_t e;
+  if (groups <= 4) e = launch_phi4<4>(p, st);
+  else if (groups <= 8) e = launch_phi4<8>(p, st);
+  else if (groups <= 16) e = launch_phi4<16>(p, st);
+  else if (groups <= 32) e = launch_phi4<32>(p, st);
+  else e = launch_phi4<64>(p, st);
+  if (e != hipSuccess) return sdi::fail(ctx->err, SD_ERR_HIP, "sd_langevin_window_phi4: %s", hipGetErrorString(e));
   return SD_OK;
 }

@@ -4,7 +4,7 @@ from __future__ import annotations
 import torch
 
 from .binding import Context, Denoiser
-from .sampler import DiffusionSampler, EfficientFrozenSampler, IndependentDrafterSampler, LangevinSampler
+from .sampler import DiffusionSampler, EfficientFrozenSampler, IndependentDrafterSampler, LangevinSampler, Phi4LangevinSampler
 
 
 def make_context(cfg, seed=None) -> Context:
@@ -32,6 +32,8 @@ def make_sampler(cfg, B=None, out_rows=None, seed=None, drafter: str = "frozen",
     "frozen" (default) or "independent" with the draft model's parameters in ``draft_params``."""
     B = cfg.B if B is None else B
     ctx = make_context(cfg, seed)
+    if cfg.kind == "phi4":
+        return Phi4LangevinSampler(ctx, cfg.params.L, cfg.params.beta, cfg.gamma, B, out_rows)
     if drafter == "independent":
         if cfg.kind == "langevin" or draft_params is None:
             raise ValueError("the independent drafter needs a diffusion workload and draft_params")

@@ -213,3 +213,17 @@ class LangevinSampler(_SamplerBase):
         with self.timer.stage("langevin_window", B):
             self.ctx.sd_langevin_window(B, b.y, b.n, b.chain_id, self.means, self.logw, self.comp_std,
                                         self.M, self.gamma, b.y_out, b.adv, b.rejected, logratio, logu)
+
+
+class Phi4LangevinSampler(_SamplerBase):
+    """Speculative unadjusted Langevin on the phi^4 lattice energy: ``sd_langevin_window_phi4`` + ``sd_advance``."""
+
+    def __init__(self, ctx: Context, L: int, beta: float, gamma: float, B: int, out_rows: Optional[int] = None):
+        self.L, self.beta, self.gamma = L, beta, gamma
+        self._setup(ctx, B, out_rows, False)
+
+    def window(self, B: int, logratio=None, logu=None):
+        b = self.buf
+        with self.timer.stage("langevin_window", B):
+            self.ctx.sd_langevin_window_phi4(B, b.y, b.n, b.chain_id, self.L, self.beta,
+                                             self.gamma, b.y_out, b.adv, b.rejected, logratio, logu)

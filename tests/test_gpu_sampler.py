@@ -135,3 +135,67 @@ def test_langevin_free_run_small():
     assert counters[0] == cfg.B * cfg.T and diverged <= 1
     if diverged == 0:
         assert counters[1] == cw and counters[2] == rejections
+
+
+@pytest.mark.parametrize("L_,B,K,T", [(8, 300, 20, 50), (4, 70, 6, 30), (16, 40, 12, 40), (5, 33, 7, 25)])
+def test_phi4_langevin_window_matches_oracle(L_, B, K, T):
+    """The fused Langevin window on the phi^4 lattice energy against the oracle's ula_window with the
+    oracle's Phi4Energy: grids whose sites fill the lanes exactly, leave lanes idle (5 x 5) or take a
+    whole wavefront (16 x 16); chains at ragged positions, near the end of the run."""
+    from oracle.langevin import Phi4Energy
+    rng = np.random.default_rng(12)
+    d = L_ * L_
+    cfg = W.make_config("phi4", B=B, d=d, K=K, T=T)
+    beta, gamma = cfg.params.beta, cfg.gamma
+    E = Phi4Energy(L_, beta)
+    ctx = make_context(cfg.schedule, d, K, seed=31)
+    # ordered states with noise, the regime the chain lives in
+    x = as_f32_f64(rng.choice([-1.0, 1.0], size=(B, 1)) + 0.15 * rng.standard_normal((B, d)))
+    n = rng.integers(0, T, size=B)
+    n[:3] = [T - 1, T - 2, 0]
+    ids = rng.permutation(5000)[:B].astype(np.int64)
+    xo, adv, rej, lr, lu = L.ula_window(E, x, n, ids, K, T, gamma, seed=31)
+    gx = torch.full((B, d), 9.0, dtype=torch.float32, device="cuda")
+    gadv = torch.zeros(B, dtype=torch.int32, device="cuda")
+    grej = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    glr = torch.full((B, K), 5.0, dtype=torch.float32, device="cuda")
+    glu = torch.full((B, K), 5.0, dtype=torch.float32, device="cuda")
+    ctx.sd_langevin_window_phi4(B, f32(x), dev(n, torch.int32), dev(ids, torch.int64), L_, beta, gamma, gx, gadv, grej, glr, glu)
+
+    class R:
+        pass
+    R.adv, R.logu, R.logratio = adv, lu, lr
+    nbad, near = decisions_match(host(gadv), R)
+    print(f"[phi4 L={L_}] rejected {rej.mean():.2f}, mean adv {adv.mean():.2f}, mismatches {nbad} (near ties {near})")
+    assert nbad == near
+    same = host(gadv) == adv
+    assert same.mean() > 0.9
+    assert np.array_equal(host(grej)[same].astype(bool), rej[same])
+    assert rel_err(host(gx)[same], xo[same]) < TOL
+    for b in np.nonzero(same)[0]:
+        a = adv[b]
+        assert np.max(np.abs(host(glu)[b, :a] - lu[b, :a])) < 1e-5
+        assert np.max(np.abs(host(glr)[b, :a] - lr[b, :a]) / np.maximum(1, np.abs(lr[b, :a]))) < 1e-5
+        assert np.all(host(glr)[b, a:] == 0) and np.all(host(glu)[b, a:] == 0)
+
+
+def test_phi4_langevin_free_run_and_argument_checks():
+    from paper_2501_05370_amd.binding import SDError
+    from paper_2501_05370_amd.runner import make_sampler
+    from oracle.langevin import Phi4Energy
+    cfg = W.make_config("phi4", B=64, T=120)
+    smp = make_sampler(cfg)
+    out, counters = smp.run(torch.arange(cfg.B, dtype=torch.int64, device="cuda"))
+    ref, cw, rejections = L.ula_sample(Phi4Energy(cfg.params.L, cfg.params.beta), cfg.B, cfg.d, cfg.K, cfg.T, cfg.gamma,
+                                       seed=cfg.seed)
+    err = np.max(np.abs(host(out) - ref), axis=1) / np.maximum(1.0, np.abs(ref).max(axis=1))
+    diverged = int((err > 1e-3).sum())
+    print(f"[phi4 free run] counters {counters}, oracle chain-windows {cw} rejections {rejections}, off-path {diverged}")
+    assert counters[0] == cfg.B * cfg.T and diverged <= 2
+    if diverged == 0:
+        assert counters[1] == cw and counters[2] == rejections
+    b = smp.buf
+    with pytest.raises(SDError):                              # grid side that does not match the context's d
+        smp.ctx.sd_langevin_window_phi4(4, b.y, b.n, b.chain_id, 7, 100.0, 1e-3, b.y_out, b.adv, b.rejected)
+    with pytest.raises(SDError):
+        smp.ctx.sd_langevin_window_phi4(4, b.y, b.n, b.chain_id, 8, 100.0, -1.0, b.y_out, b.adv, b.rejected)

@@ -17,7 +17,7 @@ def _declared():
     for h in ("sd.h", "sdden.h"):
         text = open(os.path.join(ROOT, "include", h)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(sd(?:den)?_[a-z_]+)\s*\(", text))
+        names |= set(re.findall(r"\b(sd(?:den)?_[a-z0-9_]+)\s*\(", text))
     return names
 
 

@@ -114,6 +114,12 @@ class LowRankGaussianParams:
 
 
 @dataclass
+class Phi4Params:
+    L: int                 # grid side, d = L*L sites numbered row by row, periodic
+    beta: float            # coupling
+
+
+@dataclass
 class MLPParams:
     """x0-predicting MLP: [x ; temb(k)] -> H -> H -> d, SiLU, weights stored as bf16 bit patterns."""
     d: int
@@ -227,7 +233,7 @@ def make_config(name: str, *, B: Optional[int] = None, d: Optional[int] = None,
     noise comes from the counter-based generator each side implements for itself.
     """
     name = name.lower()
-    idx = {"c1": 1, "c2": 2, "c3": 3, "c4": 4, "c5": 5}[name]
+    idx = {"c1": 1, "c2": 2, "c3": 3, "c4": 4, "c5": 5, "phi4": 6}[name]
     rng = np.random.default_rng([seed, idx])
     if name == "c1":
         T = T or 100
@@ -259,4 +265,13 @@ def make_config(name: str, *, B: Optional[int] = None, d: Optional[int] = None,
                       langevin_schedule(T, gamma),
                       random_gmm(rng, M or 16, d, 2.0, 1.0, 1.0), gamma=float(np.float32(gamma)),
                       stands_in_for="speculative unadjusted Langevin appendix")
+    if name == "phi4":
+        # the phi^4 lattice of the Langevin appendix: 8 x 8 grid, beta = 100, step 1e-3, window 20
+        # (d = L*L; "M" is unused).  The appendix runs 1e5 iterations; the benchmark runs T of them.
+        T = T or 2000
+        L = int(round(np.sqrt(d))) if d else 8
+        gamma = 1e-3
+        return Config(name, "phi4", B or 16384, L * L, K or 20, T, seed, langevin_schedule(T, gamma),
+                      Phi4Params(L, float(np.float32(100.0))), gamma=float(np.float32(gamma)),
+                      stands_in_for="phi^4 lattice Langevin experiment (energy is analytic; no data)")
     raise ValueError(name)
