@@ -98,7 +98,7 @@ def _sampler(cfg, drafter):
     return make_sampler(cfg, drafter=drafter)
 
 
-def run_gpu(cfg, steps, warmup, stages, drafter="frozen"):
+def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1):
     import torch
     from paper_2501_05370_amd.runner import make_sampler
     from paper_2501_05370_amd.sampler import StageTimer
@@ -109,28 +109,44 @@ def run_gpu(cfg, steps, warmup, stages, drafter="frozen"):
     smp = _sampler(cfg, drafter)
     ids = torch.arange(cfg.B, dtype=torch.int64, device="cuda")
     plan = roofline_plan(cfg)
+    run_kw = {} if loop == "eager" else dict(windows_per_sync=wps, graph=(loop == "graph"))
     for w in range(warmup):
         smp.ctx.sd_set_seed(cfg.seed + 1000 + w)
-        smp.run(ids)
+        smp.run(ids, **run_kw)
     torch.cuda.synchronize()
 
     den = getattr(smp, "den", None)
-    if stages:
-        smp.timer = StageTimer()
-    elif "stage" in plan:
-        smp.timer = StageTimer([plan["stage"]])
-    if "den_which" in plan:
-        den.sdden_profile_min_rows(plan.get("den_min_rows", 0))
-        den.sdden_profile(plan["den_which"])
+    events_in_loop = loop == "eager"            # per-stage events cannot be recorded into replayed graphs
+    if events_in_loop:
+        if stages:
+            smp.timer = StageTimer()
+        elif "stage" in plan:
+            smp.timer = StageTimer([plan["stage"]])
+        if "den_which" in plan:
+            den.sdden_profile_min_rows(plan.get("den_min_rows", 0))
+            den.sdden_profile(plan["den_which"])
     smp.buf.counters.zero_()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(steps):
         smp.ctx.sd_set_seed(cfg.seed + s)
-        smp.run(ids, reset_counters=False)
+        smp.run(ids, reset_counters=False, **run_kw)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     counters = smp.buf.counters.tolist()
+    timed_note = None
+    if not events_in_loop:
+        # the roofline kernel (and the stage table) are timed in one more pass of the plain loop with the
+        # same seed: same kernels on the same data, HIP events on the launch stream
+        timed_note = "separate eager pass after the timed region (the timed passes replay HIP graphs / launch several windows per readback)"
+        smp.timer = StageTimer() if stages else (StageTimer([plan["stage"]]) if "stage" in plan else smp.timer)
+        if "den_which" in plan:
+            den.sdden_profile_min_rows(plan.get("den_min_rows", 0))
+            den.sdden_profile(plan["den_which"])
+        smp.ctx.sd_set_seed(cfg.seed)
+        _, counters_roof = smp.run(ids)
+    else:
+        counters_roof = counters
     timed = smp.timer.collect() if hasattr(smp.timer, "collect") else {}
     if "den_which" in plan:
         k_ms, k_launches = den.sdden_profile_collect()
@@ -138,18 +154,20 @@ def run_gpu(cfg, steps, warmup, stages, drafter="frozen"):
         den.sdden_profile_min_rows(0)
     else:
         k_ms, k_launches, _ = timed[plan["stage"]]
+    cw = list(counters_roof)
     if drafter == "efficient_frozen" and "den_which" in plan:
         # one call per window on the start state and all drafts but a chain's final state:
         # rows = chain-windows + sum Kt - chains finished; expressed through the counters the plan uses
-        counters = list(counters)
-        counters[4] = counters[4] + 2 * counters[1] - cfg.B * steps
-    work = plan["work"](counters)
+        cw[4] = cw[4] + 2 * cw[1] - cfg.B * (steps if events_in_loop else 1)
+    work = plan["work"](cw)
     peak, unit = PEAK[plan["peak"]]
     achieved = work * plan["scale"] / (k_ms * 1e-3) if k_ms > 0 else 0.0
     roofline = {"kernel": plan["kernel"], "bound": plan["bound"], "achieved": round(achieved, 3), "peak": peak,
                 "unit": unit, "frac": round(achieved / peak, 5), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
                 "avg_launch_us": round(1e3 * k_ms / max(1, k_launches), 3), "launches": k_launches,
                 "work_per_launch": work / max(1, k_launches)}
+    if timed_note:
+        roofline["timed_in"] = timed_note
     stage_table = {k: {"ms_total": round(v[0], 3), "launches": v[1], "us_per_launch": round(1e3 * v[0] / max(1, v[1]), 2)}
                    for k, v in timed.items()} if stages else None
     return elapsed, counters, roofline, stage_table
@@ -284,6 +302,12 @@ def main():
                     help="frozen (default, the benchmark's drafter); independent: a cheaper network of the same "
                          "family called at every window position; efficient_frozen: frozen on the prediction "
                          "carried over from the previous window, one batched target call per window (c1-c4)")
+    ap.add_argument("--loop", default=None, choices=["eager", "multi", "graph"],
+                    help="window loop: eager = one host readback of the batch size per window; multi = batch size kept "
+                         "on the device, --windows-per-sync windows per readback; graph = multi with window + advance "
+                         "replayed from a HIP graph.  Default: graph for c1, multi for c2, c5 and phi4 (whichever measured "
+                         "faster), eager for c3 and c4 (windows of milliseconds)")
+    ap.add_argument("--windows-per-sync", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the untimed extras (acceptance by position, sequential chain on the GPU)")
@@ -307,7 +331,10 @@ def main():
     steps = args.steps if args.steps is not None else {"c1": 20, "c2": 10, "c3": 3, "c4": 3, "c5": 2, "phi4": 3}[cfg.name]
     if args.drafter != "frozen" and cfg.kind in ("langevin", "phi4"):
         raise SystemExit("bench.py: the drafter variants are built for the diffusion workloads c1-c4")
-    elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages, args.drafter)
+    loop = args.loop or ({"c1": "graph", "c2": "multi", "c5": "multi", "phi4": "multi"}.get(cfg.name, "eager")
+                         if args.drafter == "frozen" else "eager")
+    elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages, args.drafter, loop,
+                                                       args.windows_per_sync)
     total_steps = counters[0]
     assert total_steps == cfg.B * cfg.T * steps, (total_steps, cfg.B, cfg.T, steps)
     line = {
@@ -319,7 +346,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.kind == "mlp" else ("f64" if cfg.kind in ("langevin", "phi4") else "f32"), "data": "synthetic",
         "config": {"workload": DESCRIPTIONS[cfg.name], "chains": cfg.B, "d": cfg.d, "window_K": cfg.K,
-                   "chain_steps_T": cfg.T, "drafter": args.drafter, "seed": cfg.seed,
+                   "chain_steps_T": cfg.T, "drafter": args.drafter, "seed": cfg.seed, "window_loop": loop,
                    "step_definition": "one full sampler pass: all chains from step 0 to T"},
         "mean_accepted_draft_length": round(counters[0] / max(1, counters[1]), 4),
         "windows_per_step": round(counters[3] / steps, 2),

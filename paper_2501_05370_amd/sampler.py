@@ -98,15 +98,78 @@ class _SamplerBase:
             self.ctx.sd_advance(B, b.y_out, b.adv, b.rejected, b.y, b.n, b.chain_id, b.out, b.B_active,
                                 b.counters)
 
-    def run(self, chain_ids: torch.Tensor, reset_counters: bool = True):
+    def run(self, chain_ids: torch.Tensor, reset_counters: bool = True, windows_per_sync: int = 1,
+            graph: bool = False):
         """All chains to step T.  Returns (out tensor indexed by chain id, counters as a list
-        [sum adv, chain-windows, rejections, windows, sum Kt])."""
+        [sum adv, chain-windows, rejections, windows, sum Kt]).
+
+        ``windows_per_sync`` > 1 (or ``graph``) keeps the batch size on the device: the kernels read
+        it from ``B_active`` (``sd_set_active_count``), the host launches that many windows with the
+        last known bound before it reads the 4 bytes back, and windows launched after the last chain
+        finished do nothing.  ``graph`` additionally captures window + advance for a bound in a HIP
+        graph (through torch.cuda.CUDAGraph) and replays it: for workloads whose windows are a few
+        tens of microseconds of kernels, launch cost is what is left.  Results do not depend on
+        either option (noise is keyed by chain id and step, never by the launch)."""
         B = self.start(chain_ids, reset_counters)
-        while B > 0:
-            self.window(B)
-            self.advance(B)
-            B = int(self.buf.B_active.item())                   # the one 4-byte readback per window
-        return self.buf.out, self.buf.counters.tolist()
+        if windows_per_sync <= 1 and not graph:
+            while B > 0:
+                self.window(B)
+                self.advance(B)
+                B = int(self.buf.B_active.item())               # the one 4-byte readback per window
+            return self.buf.out, self.buf.counters.tolist()
+        if not isinstance(self.timer, _NoTimer):
+            raise RuntimeError("stage timing records events per call: not available with windows_per_sync / graph")
+        b = self.buf
+        b.B_active.fill_(B)
+        self._set_active(b.B_active)
+        try:
+            if graph and B > 0:                                 # first window eagerly: one-time kernel attribute set-up
+                self.window(B)
+                self.advance(B)
+                B = min(B, int(b.B_active.item()))
+            while B > 0:
+                bound = self._bound(B)
+                if graph:
+                    g = self._graph(bound)
+                    for _ in range(max(1, windows_per_sync)):
+                        g.replay()
+                else:
+                    for _ in range(windows_per_sync):
+                        self.window(bound)
+                        self.advance(bound)
+                B = int(b.B_active.item())
+        finally:
+            self._set_active(None)
+        return b.out, b.counters.tolist()
+
+    def _bound(self, B: int) -> int:
+        """Launch bound for B remaining chains: B rounded up to 1/8 steps of the capacity, so that a
+        handful of graphs serves a whole run."""
+        step = max(1, self.buf.B // 8)
+        return min(self.buf.B, -(-B // step) * step)
+
+    def _set_active(self, count: Optional[torch.Tensor]):
+        self._active = count
+        self.ctx.sd_set_active_count(count)
+        if count is None and getattr(self, "den", None) is not None:
+            self.den.sdden_set_active_count(None, 1)
+            if getattr(self, "draft_den", None) is not None:
+                self.draft_den.sdden_set_active_count(None, 1)
+
+    def _den_rows(self, den, rows_per_chain: int):
+        """Before a denoiser call in device-count mode: rows beyond count * rows_per_chain are skipped."""
+        if getattr(self, "_active", None) is not None:
+            den.sdden_set_active_count(self._active, rows_per_chain)
+
+    def _graph(self, bound: int):
+        cache = self.__dict__.setdefault("_graphs", {})
+        if bound not in cache:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                self.window(bound)
+                self.advance(bound)
+            cache[bound] = g
+        return cache[bound]
 
 
 class DiffusionSampler(_SamplerBase):
@@ -118,6 +181,7 @@ class DiffusionSampler(_SamplerBase):
         """One pass of the while-loop body for the first B chains of the buffers."""
         b, ctx, den, d, K, t = self.buf, self.ctx, self.den, self.ctx.d, self.ctx.K, self.timer
         with t.stage("predict_start", B):
+            self._den_rows(den, 1)
             den.sdden_eval(B, b.y, b.n, b.D0)                   # D0 = D(y_n, n)
         with t.stage("draft", B):
             ctx.sd_draft(B, b.y, b.n, b.chain_id, b.D0, b.Ytilde, b.krow)
@@ -125,6 +189,7 @@ class DiffusionSampler(_SamplerBase):
             # row (b,j) of Ytilde feeds row (b,j+1) of Dq: same flat layout shifted by one row;
             # the last row of every chain is masked by krow, so the shifted write stays in bounds
             with t.stage("predict_drafts", B):
+                self._den_rows(den, K)
                 den.sdden_eval(B * K, b.Ytilde.view(-1, d), b.krow.view(-1), b.Dq.view(-1, d)[1:])
         lr, lu = diagnostics if diagnostics is not None else (None, None)
         with t.stage("verify", B):
@@ -151,9 +216,11 @@ class IndependentDrafterSampler(_SamplerBase):
     def window(self, B: int, diagnostics=None):
         b, ctx, d, K, t = self.buf, self.ctx, self.ctx.d, self.ctx.K, self.timer
         with t.stage("predict_start", B):
+            self._den_rows(self.den, 1)
             self.den.sdden_eval(B, b.y, b.n, b.D0)              # target at the window start
         prev, kprev = b.y, b.n
         with t.stage("draft", B):
+            self._den_rows(self.draft_den, 1)
             for j in range(1, K + 1):
                 self.draft_den.sdden_eval(B, prev, kprev, b.Dp)
                 nxt, knext = b.cur[j & 1], b.kcur[j & 1]
@@ -161,6 +228,7 @@ class IndependentDrafterSampler(_SamplerBase):
                 prev, kprev = nxt, knext
         if K > 1:
             with t.stage("predict_drafts", B):
+                self._den_rows(self.den, K)
                 self.den.sdden_eval(B * K, b.Ytilde.view(-1, d), b.krow.view(-1), b.Dq.view(-1, d)[1:])
         lr, lu = diagnostics if diagnostics is not None else (None, None)
         with t.stage("verify", B):
@@ -195,6 +263,7 @@ class EfficientFrozenSampler(_SamplerBase):
         with t.stage("draft", B):
             ctx.sd_draft(B, b.y, b.n, b.chain_id, b.Dfz, b.X_ext, b.krow_ext)
         with t.stage("predict_drafts", B):
+            self._den_rows(self.den, K + 1)
             self.den.sdden_eval(B * (K + 1), b.X_ext.view(-1, d), b.krow_ext.view(-1), b.Dq_ext.view(-1, d))
         lr, lu = diagnostics if diagnostics is not None else (None, None)
         with t.stage("verify", B):
