@@ -101,6 +101,11 @@ int sd_set_temperature(sd_ctx* ctx, float tau);
  * only the first min(B, *count) chains as present, so a fixed launch sequence (for instance a
  * captured HIP graph) keeps working while sd_advance shrinks the batch.  NULL restores B.        */
 int sd_set_active_count(sd_ctx* ctx, const int32_t* count);
+/* Optional bf16 image of the drafts: when set (dev, same shape and layout as the Ytilde argument of
+ * sd_draft, 16-byte aligned), sd_draft also writes every drafted value rounded to bf16
+ * (round-to-nearest-even, bit patterns) there, so that a network with bf16 inputs needs no
+ * conversion pass over the fp32 drafts (sdden_eval_mirror).  NULL (default) switches it off. */
+int sd_set_draft_mirror(sd_ctx* ctx, uint16_t* Ytilde_bf16);
 /* EXPLICIT mode only, optional: the target prediction at the window start, D(y_n, n), as its own
  * [B,d] array (dev).  When set, sd_verify reads it wherever it would read row 0 of Dq, so the
  * window-start call and the batched call on the drafts can write to separate dense outputs.

@@ -57,6 +57,13 @@ int sdden_reserve(sdden* den, int32_t Rmax);
 int sdden_eval(sdden* den, int32_t R, const float* X, const int32_t* krow, float* out,
                void* stream);
 
+/* sdden_eval for a caller that also holds the rows as bf16 (bit patterns, round-to-nearest-even of
+ * the same fp32 values; sd_draft can write this image next to the fp32 drafts, see
+ * sd_set_draft_mirror in sd.h).  The MLP reads its first layer's input from Xbf16 and skips its
+ * own conversion pass; the other denoisers ignore it.  Rows with krow < 0 need no valid image. */
+int sdden_eval_mirror(sdden* den, int32_t R, const float* X, const uint16_t* Xbf16,
+                      const int32_t* krow, float* out, void* stream);
+
 /* Optional device-resident row limit: when `count` (dev int32) is set, only rows
  * r < min(R, *count * rows_per_chain) are evaluated, which lets a fixed launch sequence follow
  * the batch as sd_advance shrinks it (see sd_set_active_count).  NULL removes the limit. */

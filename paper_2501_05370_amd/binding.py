@@ -48,6 +48,8 @@ _SIGNATURES = {
     "sd_draft_step": (c_int, [c_void_p, c_int32, c_int32] + [c_void_p] * 10),
     "sd_set_start_prediction": (c_int, [c_void_p, c_void_p]),
     "sd_set_carry": (c_int, [c_void_p, c_void_p, c_void_p]),
+    "sd_set_draft_mirror": (c_int, [c_void_p, c_void_p]),
+    "sdden_eval_mirror": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "sd_verify": (c_int, [c_void_p, c_int32] + [c_void_p] * 12),
     "sd_advance": (c_int, [c_void_p, c_int32] + [c_void_p] * 10),
     "sd_langevin_window": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -172,6 +174,11 @@ class Context:
         self._keep_start = D_start
         self._check(self._lib.sd_set_start_prediction(self._h, ptr), "sd_set_start_prediction")
 
+    def sd_set_draft_mirror(self, mirror: Optional[torch.Tensor]):
+        """mirror: int16 tensor holding bf16 bit patterns, shape of Ytilde."""
+        self._keep_mirror = mirror
+        self._check(self._lib.sd_set_draft_mirror(self._h, _dev(mirror, torch.int16, "mirror", True)), "sd_set_draft_mirror")
+
     def sd_set_carry(self, Dq_ext: Optional[torch.Tensor], D_frozen: Optional[torch.Tensor]):
         self._keep_carry = (Dq_ext, D_frozen)
         self._check(self._lib.sd_set_carry(self._h, _dev(Dq_ext, torch.float32, "Dq_ext", True),
@@ -291,7 +298,9 @@ class Denoiser:
         h = c_void_p()
         rc = lib.sdden_mlp_create(p.d, p.H, p.E, W1.ctypes.data, b1.ctypes.data, W2.ctypes.data,
                                   b2.ctypes.data, W3.ctypes.data, b3.ctypes.data, T, Rmax, ctypes.byref(h))
-        return cls(cls._created(rc, h, "sdden_mlp_create"), p.d)
+        den = cls(cls._created(rc, h, "sdden_mlp_create"), p.d)
+        den.wants_bf16 = True                      # first layer reads bf16: sdden_eval_mirror saves a conversion pass
+        return den
 
     def _check(self, rc, what):
         if rc != 0:
@@ -304,6 +313,14 @@ class Denoiser:
                 raise SDError(f"{nm}: need a contiguous {dt} CUDA tensor")
         self._check(self._lib.sdden_eval(self._h, R, X.data_ptr(), krow.data_ptr(), out.data_ptr(), _stream()),
                     "sdden_eval")
+
+    def sdden_eval_mirror(self, R, X, Xbf16, krow, out):
+        for t, dt, nm in ((X, torch.float32, "X"), (Xbf16, torch.int16, "Xbf16"), (krow, torch.int32, "krow"),
+                          (out, torch.float32, "out")):
+            if not t.is_cuda or t.dtype != dt or not t.is_contiguous():
+                raise SDError(f"{nm}: need a contiguous {dt} CUDA tensor")
+        self._check(self._lib.sdden_eval_mirror(self._h, R, X.data_ptr(), Xbf16.data_ptr(), krow.data_ptr(),
+                                                out.data_ptr(), _stream()), "sdden_eval_mirror")
 
     def sdden_reserve(self, Rmax: int):
         self._check(self._lib.sdden_reserve(self._h, Rmax), "sdden_reserve")

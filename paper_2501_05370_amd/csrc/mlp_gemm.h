@@ -31,7 +31,8 @@ constexpr int BK = 64;
 constexpr int kRowPad = 256;      // row capacity of A operands must be a multiple of this
 
 struct Args {
-  const uint16_t* A;     // [>= tiles*BM, Kdim] bf16, dense
+  const uint16_t* A;     // [>= tiles*BM, Kdim] bf16, dense; or, with arow, the rows arow[m] of a larger matrix
+  const int32_t* arow;   // optional gather index for the rows of A (dense row m reads A[arow[m]])
   const uint16_t* Bt;    // [N, Kdim] bf16 (weights, transposed: row = output feature)
   int N, Kdim;
   const int32_t* count;  // device: M
@@ -69,7 +70,7 @@ __device__ __forceinline__ void barrier_keep_loads() { asm volatile("s_waitcnt l
 
 // EPI 1: out = bf16(silu(acc + bias[krow[src]][n]));  EPI 2: out = bf16(silu(acc + bias[n]));
 // EPI 3: outf[src][n] = acc + bias[n].
-template <int BM, int BN, int WM, int WN, int EPI, int NS, int PM = 4, int PN = 8>
+template <int BM, int BN, int WM, int WN, int EPI, int NS, bool GATHER = false, int PM = 4, int PN = 8>
 __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -105,6 +106,16 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   const unsigned char* b_lane = reinterpret_cast<const unsigned char*>(p.Bt) +
                                 (static_cast<size_t>(tile_n) * BN + 8 * wave + lrow) * Kd * 2 + 16 * lchunk;
   const size_t pass_stride = static_cast<size_t>(8 * NW) * Kd * 2;
+  // gathered A: one source row per load pass (rows past M repeat the last one: computed, never stored)
+  const unsigned char* a_src[GATHER ? APASS : 1];
+  if (GATHER) {
+#pragma unroll
+    for (int i = 0; i < APASS; ++i) {
+      int r = tile_m * BM + 8 * (i * NW + wave) + lrow;
+      r = r < M ? r : M - 1;
+      a_src[i] = reinterpret_cast<const unsigned char*>(p.A) + static_cast<size_t>(p.arow[r]) * Kd * 2 + 16 * lchunk;
+    }
+  }
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -119,7 +130,7 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
 #define MLPGEMM_FETCH(s_, k0)                                                                        \
   do {                                                                                                 \
     _Pragma("unroll") for (int i_ = 0; i_ < APASS; ++i_)                                               \
-        __builtin_amdgcn_global_load_lds((gbl_ptr)(a_lane + i_ * pass_stride + (k0) * 2),              \
+        __builtin_amdgcn_global_load_lds((gbl_ptr)((GATHER ? a_src[GATHER ? i_ : 0] : a_lane + i_ * pass_stride) + (k0) * 2), \
                                          (lds_ptr)(As + (s_) * BM * 128 + (i_ * NW + wave) * 1024), 16, 0, 0); \
     _Pragma("unroll") for (int i_ = 0; i_ < BPASS; ++i_)                                               \
         __builtin_amdgcn_global_load_lds((gbl_ptr)(b_lane + i_ * pass_stride + (k0) * 2),              \
@@ -190,13 +201,13 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int NS, int PM = 4, int PN = 8>
+template <int BM, int BN, int WM, int WN, int EPI, int NS, bool GATHER = false, int PM = 4, int PN = 8>
 hipError_t launch(const Args& a, int Rmax, hipStream_t st) {
   constexpr size_t shmem = NS * static_cast<size_t>(BM + BN) * 128;
   static_assert(NS >= 2 && shmem <= 160 * 1024, "ring must fit the 160 KiB of LDS");
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, EPI, NS, PM, PN>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, EPI, NS, GATHER, PM, PN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -204,7 +215,7 @@ hipError_t launch(const Args& a, int Rmax, hipStream_t st) {
   const int tiles_m = (Rmax + BM - 1) / BM, tiles_n = a.N / BN;
   const int patches = ((tiles_m + PM - 1) / PM) * ((tiles_n + PN - 1) / PN);
   const int grid = (patches * PM * PN + 7) / 8 * 8;
-  hipLaunchKernelGGL((kernel<BM, BN, WM, WN, EPI, NS, PM, PN>), dim3(grid), dim3(64 * WM * WN), shmem, st, a);
+  hipLaunchKernelGGL((kernel<BM, BN, WM, WN, EPI, NS, GATHER, PM, PN>), dim3(grid), dim3(64 * WM * WN), shmem, st, a);
   return hipGetLastError();
 }
 

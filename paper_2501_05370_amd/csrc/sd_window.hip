@@ -84,6 +84,7 @@ struct DraftArgs {
   const int32_t* n;
   const int64_t* id;
   float* Ytil;
+  uint16_t* mirror;      // optional bf16 image of Ytil (round-to-nearest-even), same layout
   int32_t* krow;
   const float *a, *c, *sigma;
   const int32_t* active;
@@ -92,6 +93,25 @@ struct DraftArgs {
                          // (K, 0; or K+1, 1 with row 0 = a copy of y for the one batched target call)
   uint64_t seed;
 };
+
+__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
+  const __bf16 a = static_cast<__bf16>(lo), b = static_cast<__bf16>(hi);
+  uint16_t ua, ub;
+  __builtin_memcpy(&ua, &a, 2);
+  __builtin_memcpy(&ub, &b, 2);
+  return static_cast<uint32_t>(ua) | (static_cast<uint32_t>(ub) << 16);
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_mirror(uint16_t* dst, const float v[4], int i0, int d) {
+  if (VEC == 4) {
+    *reinterpret_cast<uint2*>(dst) = make_uint2(bf16_pair(v[0], v[1]), bf16_pair(v[2], v[3]));
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (i0 + e < d) dst[e] = static_cast<uint16_t>(bf16_pair(v[e], 0.f) & 0xffffu);
+  }
+}
 
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
@@ -132,6 +152,7 @@ __global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
       for (int e = 0; e < 4; ++e)
         if (i0 + e < p.d) dst[e] = prev[e];
     }
+    if (p.mirror) store_mirror<VEC>(p.mirror + static_cast<int64_t>(b) * p.rs * p.d + i0, prev, i0, p.d);
     if (blk == 0) p.krow[static_cast<int64_t>(b) * p.rs] = n;
   }
   for (int j = 0; j < p.K; ++j) {       // position j+1 of the window, produces state n+j+1
@@ -156,6 +177,7 @@ __global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
       for (int e = 0; e < 4; ++e)
         if (i0 + e < p.d) dst[e] = out[e];
     }
+    if (p.mirror) store_mirror<VEC>(p.mirror + (static_cast<int64_t>(b) * p.rs + p.roff + j) * p.d + i0, out, i0, p.d);
     if (blk == 0) {
       // which drafted states the target must evaluate: all but the last one; with the extra row also the
       // last one (its prediction is the next window's frozen vector) unless it is the chain's final state
@@ -676,6 +698,12 @@ int sd_set_carry(sd_ctx* ctx, const float* Dq_ext, float* D_frozen) {
   return SD_OK;
 }
 
+int sd_set_draft_mirror(sd_ctx* ctx, uint16_t* Ytilde_bf16) {
+  if (!ctx) return SD_ERR_ARG;
+  ctx->draft_mirror = Ytilde_bf16;
+  return SD_OK;
+}
+
 int sd_set_start_prediction(sd_ctx* ctx, const float* D_start) {
   if (!ctx) return SD_ERR_ARG;
   ctx->start_pred = D_start;
@@ -729,7 +757,7 @@ int sd_draft(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int
     return sdi::fail(ctx->err, SD_ERR_ARG, "sd_draft: bad argument");
   if (B == 0) return SD_OK;
   DraftArgs p;
-  p.y = y; p.D0 = D0; p.n = n; p.id = chain_id; p.Ytil = Ytilde; p.krow = krow;
+  p.y = y; p.D0 = D0; p.n = n; p.id = chain_id; p.Ytil = Ytilde; p.krow = krow; p.mirror = ctx->draft_mirror;
   p.a = ctx->dev_a; p.c = ctx->dev_c; p.sigma = ctx->dev_sigma; p.active = ctx->active;
   p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.nblk = (ctx->d + 3) / 4; p.seed = ctx->seed;
   const bool ext = ctx->mode == SD_DRAFT_FROZEN_REUSED;
@@ -737,7 +765,8 @@ int sd_draft(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int
   const int64_t total = static_cast<int64_t>(B) * p.nblk;
   const int64_t grid = (total + kBlock - 1) / kBlock;
   if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_draft: B*d too large");
-  const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y) && sdi::aligned16(D0) && sdi::aligned16(Ytilde);
+  const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y) && sdi::aligned16(D0) && sdi::aligned16(Ytilde) &&
+                   sdi::aligned16(ctx->draft_mirror);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (vec) hipLaunchKernelGGL(draft_frozen_kernel<4>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st, p);
   else     hipLaunchKernelGGL(draft_frozen_kernel<1>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st, p);

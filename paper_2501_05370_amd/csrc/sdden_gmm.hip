@@ -208,6 +208,16 @@ int sdden_eval(sdden* den, int32_t R, const float* X, const int32_t* krow, float
   return den->eval(R, X, krow, out, static_cast<hipStream_t>(stream));
 }
 
+int sdden_eval_mirror(sdden* den, int32_t R, const float* X, const uint16_t* Xbf16, const int32_t* krow, float* out,
+                      void* stream) {
+  if (!den) return SD_ERR_ARG;
+  if (R < 0 || (R > 0 && (!X || !Xbf16 || !krow || !out)))
+    return sdi::fail(den->err, SD_ERR_ARG, "sdden_eval_mirror: bad argument");
+  if (R == 0) return SD_OK;
+  den->prof.cur_rows = R;
+  return den->eval_mirror(R, X, Xbf16, krow, out, static_cast<hipStream_t>(stream));
+}
+
 int sdden_reserve(sdden* den, int32_t Rmax) {
   if (!den) return SD_ERR_ARG;
   if (Rmax <= 0) return sdi::fail(den->err, SD_ERR_ARG, "sdden_reserve: Rmax must be > 0");

@@ -35,6 +35,11 @@ struct sdden {
   virtual int eval(int R, const float* X, const int32_t* krow, float* out, hipStream_t st) = 0;
   // Allocate whatever per-call scratch evaluations of up to R rows need (setup time only).
   virtual int reserve(int R) { (void)R; return SD_OK; }
+  // X with a caller-provided bf16 image of the same rows; denoisers without a use for it ignore it
+  virtual int eval_mirror(int R, const float* X, const uint16_t* Xbf16, const int32_t* krow, float* out, hipStream_t st) {
+    (void)Xbf16;
+    return eval(R, X, krow, out, st);
+  }
   int d = 0, T = 0;
   sdden_profiler prof;
   const int32_t* active = nullptr;   // optional device-side chain count

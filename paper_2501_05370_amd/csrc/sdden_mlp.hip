@@ -63,16 +63,16 @@ float bf16_bits_to_float(uint16_t b) {
 // three quarters full; otherwise 128x128 (4 wavefronts, two stages, two workgroups per CU) when
 // that gives 512 tiles or more, else 64x128: with at most one workgroup per CU (the window-start
 // call) as a four-stage ring, with more as two stages so that three workgroups share a CU.
-template <int EPI>
+template <int EPI, bool GATHER = false>
 int launch_gemm(const mlpgemm::Args& a, int R, hipStream_t st, std::string& err) {
   const int t256 = ((R + 255) / 256) * (a.N / 256);
   const int t128 = ((R + 127) / 128) * (a.N / 128);
   const int t64 = ((R + 63) / 64) * (a.N / 128);
   hipError_t e;
-  if (4 * t256 >= 3 * ((t256 + 255) / 256) * 256) e = mlpgemm::launch<256, 256, 2, 4, EPI, 2>(a, R, st);
-  else if (t128 >= 512) e = mlpgemm::launch<128, 128, 2, 2, EPI, 2>(a, R, st);
-  else if (t64 > 256) e = mlpgemm::launch<64, 128, 2, 2, EPI, 2>(a, R, st);
-  else e = mlpgemm::launch<64, 128, 2, 2, EPI, 4>(a, R, st);
+  if (4 * t256 >= 3 * ((t256 + 255) / 256) * 256) e = mlpgemm::launch<256, 256, 2, 4, EPI, 2, GATHER>(a, R, st);
+  else if (t128 >= 512) e = mlpgemm::launch<128, 128, 2, 2, EPI, 2, GATHER>(a, R, st);
+  else if (t64 > 256) e = mlpgemm::launch<64, 128, 2, 2, EPI, 2, GATHER>(a, R, st);
+  else e = mlpgemm::launch<64, 128, 2, 2, EPI, 4, GATHER>(a, R, st);
   if (e != hipSuccess) return sdi::fail(err, SD_ERR_HIP, "mlp gemm launch: %s", hipGetErrorString(e));
   return SD_OK;
 }
@@ -112,21 +112,39 @@ struct MlpDenoiser final : sdden {
   }
 
   int eval(int R, const float* X, const int32_t* krow, float* out, hipStream_t st) override {
+    return eval_impl(R, X, nullptr, krow, out, st);
+  }
+  int eval_mirror(int R, const float* X, const uint16_t* Xbf16, const int32_t* krow, float* out, hipStream_t st) override {
+    return eval_impl(R, X, Xbf16, krow, out, st);
+  }
+
+  // With a bf16 image of the rows the first GEMM gathers its A rows from it and no conversion pass runs.
+  int eval_impl(int R, const float* X, const uint16_t* Xbf16, const int32_t* krow, float* out, hipStream_t st) {
     if (R > cap_rows)
       return sdi::fail(err, SD_ERR_WORKSPACE, "sdden_eval(mlp): %d rows exceed the %d reserved (sdden_reserve)", R, cap_rows);
     if (!sdi::aligned16(X)) return sdi::fail(err, SD_ERR_ARG, "sdden_eval(mlp): X must be 16-byte aligned");
     hipLaunchKernelGGL(sdrows::compact_rows_kernel, dim3(1), dim3(sdrows::kScan), 0, st, krow, rowidx, count,
                        active, rows_per_chain, R);
-    const int64_t chunks = static_cast<int64_t>(R) * (d / 8);
-    const int cgrid = static_cast<int>(std::min<int64_t>((chunks + kThreads - 1) / kThreads, 256 * 32));
-    hipLaunchKernelGGL(gather_convert_kernel, dim3(cgrid), dim3(kThreads), 0, st, X, rowidx, count, Xb, d);
     mlpgemm::Args a;
-    a.count = count; a.rowidx = rowidx; a.krow = krow;
+    a.count = count; a.rowidx = rowidx; a.krow = krow; a.arow = nullptr;
     int rc;
-    a.A = Xb; a.Bt = W1t; a.N = H; a.Kdim = d; a.bias = tb; a.outb = H1; a.outf = nullptr;
-    prof.mark(1, st);
-    rc = launch_gemm<1>(a, R, st, err);
-    prof.mark(1, st);
+    a.Bt = W1t; a.N = H; a.Kdim = d; a.bias = tb; a.outb = H1; a.outf = nullptr;
+    if (Xbf16) {
+      if (!sdi::aligned16(Xbf16)) return sdi::fail(err, SD_ERR_ARG, "sdden_eval_mirror(mlp): Xbf16 must be 16-byte aligned");
+      a.A = Xbf16; a.arow = rowidx;
+      prof.mark(1, st);
+      rc = launch_gemm<1, true>(a, R, st, err);
+      prof.mark(1, st);
+    } else {
+      const int64_t chunks = static_cast<int64_t>(R) * (d / 8);
+      const int cgrid = static_cast<int>(std::min<int64_t>((chunks + kThreads - 1) / kThreads, 256 * 32));
+      hipLaunchKernelGGL(gather_convert_kernel, dim3(cgrid), dim3(kThreads), 0, st, X, rowidx, count, Xb, d);
+      a.A = Xb;
+      prof.mark(1, st);
+      rc = launch_gemm<1>(a, R, st, err);
+      prof.mark(1, st);
+    }
+    a.arow = nullptr;
     if (rc) return rc;
     a.A = H1; a.Bt = W2t; a.N = H; a.Kdim = H; a.bias = b2; a.outb = H2;
     prof.mark(2, st);

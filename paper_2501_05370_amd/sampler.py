@@ -176,6 +176,9 @@ class DiffusionSampler(_SamplerBase):
     def __init__(self, ctx: Context, den: Denoiser, B: int, out_rows: Optional[int] = None):
         self.den = den
         self._setup(ctx, B, out_rows, True)
+        # a network with bf16 inputs gets the drafts as bf16 straight from the draft kernel
+        self.mirror = (torch.zeros(B, ctx.K, ctx.d, dtype=torch.int16, device="cuda")
+                       if getattr(den, "wants_bf16", False) else None)
 
     def window(self, B: int, diagnostics=None):
         """One pass of the while-loop body for the first B chains of the buffers."""
@@ -184,13 +187,19 @@ class DiffusionSampler(_SamplerBase):
             self._den_rows(den, 1)
             den.sdden_eval(B, b.y, b.n, b.D0)                   # D0 = D(y_n, n)
         with t.stage("draft", B):
+            ctx.sd_set_draft_mirror(self.mirror)
             ctx.sd_draft(B, b.y, b.n, b.chain_id, b.D0, b.Ytilde, b.krow)
+            ctx.sd_set_draft_mirror(None)
         if K > 1:
             # row (b,j) of Ytilde feeds row (b,j+1) of Dq: same flat layout shifted by one row;
             # the last row of every chain is masked by krow, so the shifted write stays in bounds
             with t.stage("predict_drafts", B):
                 self._den_rows(den, K)
-                den.sdden_eval(B * K, b.Ytilde.view(-1, d), b.krow.view(-1), b.Dq.view(-1, d)[1:])
+                if self.mirror is not None:
+                    den.sdden_eval_mirror(B * K, b.Ytilde.view(-1, d), self.mirror.view(-1, d), b.krow.view(-1),
+                                          b.Dq.view(-1, d)[1:])
+                else:
+                    den.sdden_eval(B * K, b.Ytilde.view(-1, d), b.krow.view(-1), b.Dq.view(-1, d)[1:])
         lr, lu = diagnostics if diagnostics is not None else (None, None)
         with t.stage("verify", B):
             ctx.sd_verify(B, b.y, b.n, b.chain_id, b.D0, b.Dq, b.Ytilde, b.y_out, b.adv, b.rejected, lr, lu)

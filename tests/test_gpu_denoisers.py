@@ -69,6 +69,14 @@ def test_mlp_denoiser_matches_oracle(d, H, E, T, R):
     g.sdden_eval(R, f32(x), dev(k2, torch.int32), out2)
     assert rel_err(host(out2)[k >= 0], den(x[k >= 0], k2[k >= 0])) < 2e-2
     assert np.abs(host(out2)[k >= 0] - got[k >= 0]).max() > 1e-3
+    # with a bf16 image of the rows (what sd_draft can write) the first GEMM gathers from it and the
+    # conversion pass is skipped: the result must be the same bits; masked rows carry garbage in the image
+    xg = f32(x)
+    img = xg.to(torch.bfloat16).view(torch.int16).contiguous()
+    img[dev(k, torch.int32) < 0] = 0x7fc0
+    out3 = torch.full((R, d), 777.0, dtype=torch.float32, device="cuda")
+    g.sdden_eval_mirror(R, xg, img, dev(k, torch.int32), out3)
+    assert np.array_equal(host(out3), got)
 
 
 def test_mlp_denoiser_full_width_sampled_rows():

@@ -247,3 +247,25 @@ def test_whole_window_pipeline_matches_oracle(name, kw):
         assert rel_err(host(b.y)[:Ba], y_ref) < 5 * TOL
         done = np.ones(B, dtype=bool); done[id_ref] = False
         assert rel_err(host(b.out)[done], out_ref[done]) < 5 * TOL
+
+
+def test_draft_writes_the_bf16_image_of_the_drafts():
+    """sd_set_draft_mirror: every drafted value also lands as bf16 (round to nearest even) in the image;
+    both the vectorised and the scalar (d % 4 != 0) kernels, frozen and K+1-row layouts."""
+    from paper_2501_05370_amd.binding import SD_DRAFT_FROZEN_REUSED
+    for d, mode in ((64, None), (37, None), (64, SD_DRAFT_FROZEN_REUSED)):
+        cfg = W.make_config("c2", B=50, d=d, T=40)
+        ctx = make_context(cfg.schedule, d, cfg.K, seed=4, mode=mode)
+        rng = np.random.default_rng(2)
+        rows = cfg.K + (1 if mode else 0)
+        y = f32(rng.standard_normal((cfg.B, d)) * 2); D0 = f32(rng.standard_normal((cfg.B, d)))
+        n = dev(rng.integers(0, cfg.T, size=cfg.B), torch.int32); ids = dev(np.arange(cfg.B), torch.int64)
+        Yt = torch.zeros(cfg.B, rows, d, device="cuda"); kr = torch.zeros(cfg.B, rows, dtype=torch.int32, device="cuda")
+        img = torch.full((cfg.B, rows, d), 0x1234, dtype=torch.int16, device="cuda")
+        ctx.sd_set_draft_mirror(img)
+        ctx.sd_draft(cfg.B, y, n, ids, D0, Yt, kr)
+        ctx.sd_set_draft_mirror(None)
+        assert torch.equal(img, Yt.to(torch.bfloat16).view(torch.int16))
+        Yt2 = torch.zeros_like(Yt); img.fill_(0x1234)
+        ctx.sd_draft(cfg.B, y, n, ids, D0, Yt2, kr)         # switched off again: image untouched, drafts equal
+        assert torch.equal(Yt2, Yt) and bool((img == 0x1234).all())
