@@ -43,7 +43,7 @@ DESCRIPTIONS = {
 # HBM bytes per launch of the roofline kernel (fetched * 2.0 + written * 1.0 of the rocprofv3 FETCH_SIZE /
 # WRITE_SIZE counters, the factors being what the same counters read for a plain device copy), taken from
 # profiles/hbm_traffic_all_kernels_c4.md; workloads without such a counter run report null
-MEASURED_TRAFFIC_BYTES = {"c4": 1495.6e6}
+MEASURED_TRAFFIC_BYTES = {"c4": 1233.0e6}
 
 # published MI355X peaks used as roofline denominators
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "mfma_fp32": (157.3, "TFLOP/s"),
@@ -59,9 +59,10 @@ def roofline_plan(cfg):
         H = cfg.params.H
         # the batched evaluation of the drafted states (rows = sum Kt - chain-windows); the window-start
         # call (one row per chain, a smaller tile) is left out of this figure
-        return dict(kernel="mlpgemm::kernel<256,256,2,4,EPI=3,NS=2> layer-3 GEMM of the batched target call, rows x 4096 -> 12288, bf16 MFMA "
-                           "(largest share of the kernel time; layer 1 has the same flops and runs within 3% of it)",
-                    den_which=3, den_min_rows=cfg.B + 1, bound="mfma", peak="mfma_bf16", scale=1e-12,
+        return dict(kernel="mlpgemm::kernel<256,256,2,4,EPI=1,NS=2,GATHER> layer-1 GEMM of the batched target call, rows x 12288 -> 4096, "
+                           "bf16 MFMA, A rows gathered from the bf16 image of the drafts (largest share of the kernel time; layer 3 has the "
+                           "same flops and runs within 5% of it)",
+                    den_which=1, den_min_rows=cfg.B + 1, bound="mfma", peak="mfma_bf16", scale=1e-12,
                     work=lambda c: 2.0 * (c[4] - c[1]) * d * H)
     if cfg.kind == "lowrank":
         rpad = -(-cfg.params.U.shape[1] // 16) * 16
