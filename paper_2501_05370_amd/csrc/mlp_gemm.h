@@ -219,4 +219,187 @@ hipError_t launch(const Args& a, int Rmax, hipStream_t st) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Hand-scheduled form of the 256 x 256 x 64 tile (8 wavefronts 2 x 4, two LDS stages), used when the
+// contraction has an even number (>= 2) of 64-wide slices.  Same operands, LDS layout and epilogues
+// as the generic kernel above.  What differs is who places the waits:
+//  * fragment reads are inline-asm ds_read_b128 and every s_waitcnt lgkmcnt(n) is written by hand, the
+//    fragments it releases being operands of the wait so that no MFMA can move above it.  The compiler
+//    left to itself waits for lgkmcnt(0) at every k-step (it loses count across the loop back-edge and
+//    across inline asm), which exposes the LDS latency four times per slice;
+//  * two fragment sets alternate per 16-wide k-step: the reads of step k+1 are issued before the
+//    MFMAs of step k;
+//  * the workgroup barrier sits before the MFMAs of the slice's last k-step (all fragment reads of
+//    the stage have returned by then), so those MFMAs cover the issue of the next global loads and
+//    the first fragment reads of the next slice.
+// ---------------------------------------------------------------------------------------------
+template <int EPI, bool GATHER = false, int PM = 4, int PN = 8>
+__global__ __launch_bounds__(512) void kernel_hs(Args p) {
+  constexpr int BM = 256, BN = 256, WN = 4, NW = 8, TM = 4, TN = 2, APASS = 4, BPASS = 4;
+  extern __shared__ __align__(1024) unsigned char smem[];
+  const int M = *p.count;
+  const int tiles_n = p.N / BN;
+  int tile_m, tile_n;
+  {
+    const int per_xcd = gridDim.x / 8;
+    const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int patches_n = (tiles_n + PN - 1) / PN;
+    const int patch = L / (PM * PN), within = L % (PM * PN);
+    tile_m = (patch / patches_n) * PM + within % PM;
+    tile_n = (patch % patches_n) * PN + within / PM;
+    if (tile_n >= tiles_n) return;
+  }
+  if (tile_m * BM >= M) return;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int half = lane >> 5, l32 = lane & 31;
+  const int Kd = p.Kdim;
+  const int lrow = lane >> 3, lchunk = (lane & 7) ^ (lane >> 3);
+  const unsigned char* b_lane = reinterpret_cast<const unsigned char*>(p.Bt) +
+                                (static_cast<size_t>(tile_n) * BN + 8 * wave + lrow) * Kd * 2 + 16 * lchunk;
+  const size_t pass_stride = static_cast<size_t>(8 * NW) * Kd * 2;
+  const unsigned char* a_src[APASS];
+#pragma unroll
+  for (int i = 0; i < APASS; ++i) {
+    int r = tile_m * BM + 8 * (i * NW + wave) + lrow;
+    if (GATHER) r = p.arow[r < M ? r : M - 1];
+    a_src[i] = reinterpret_cast<const unsigned char*>(p.A) + static_cast<size_t>(r) * Kd * 2 + 16 * lchunk;
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  typedef __attribute__((address_space(3))) void* lds_ptr;
+  typedef const __attribute__((address_space(1))) void* gbl_ptr;
+  // LDS map: A stage s at s * 32 KiB, B stage s at 64 KiB + s * 32 KiB
+#define MLPHS_FETCH(s_, k0)                                                                            \
+  do {                                                                                                   \
+    _Pragma("unroll") for (int i_ = 0; i_ < APASS; ++i_)                                                 \
+        __builtin_amdgcn_global_load_lds((gbl_ptr)(a_src[i_] + (k0) * 2),                                \
+                                         (lds_ptr)(smem + (s_) * 32768 + (i_ * NW + wave) * 1024), 16, 0, 0); \
+    _Pragma("unroll") for (int i_ = 0; i_ < BPASS; ++i_)                                                 \
+        __builtin_amdgcn_global_load_lds((gbl_ptr)(b_lane + i_ * pass_stride + (k0) * 2),                \
+                                         (lds_ptr)(smem + 65536 + (s_) * 32768 + (i_ * NW + wave) * 1024), 16, 0, 0); \
+  } while (0)
+
+  // fragment addresses as LDS byte offsets: row base + swizzled chunk of k-step kk; tiles and stages are immediates
+  const int sw = l32 & 7;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
+  uint32_t a_ad[4], b_ad[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const int off = ((2 * kk + half) ^ sw) << 4;
+    a_ad[kk] = lds0 + (wm * 128 + l32) * 128 + off;
+    b_ad[kk] = lds0 + 65536 + (wn * 64 + l32) * 128 + off;
+  }
+#define MLPHS_DSREAD(dst, addr, imm) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(imm))
+#define MLPHS_READ(fa, fb, s_, kk_)                               \
+  do {                                                            \
+    MLPHS_DSREAD(fa[0], a_ad[kk_], (s_) * 32768 + 0);             \
+    MLPHS_DSREAD(fa[1], a_ad[kk_], (s_) * 32768 + 4096);          \
+    MLPHS_DSREAD(fa[2], a_ad[kk_], (s_) * 32768 + 8192);          \
+    MLPHS_DSREAD(fa[3], a_ad[kk_], (s_) * 32768 + 12288);         \
+    MLPHS_DSREAD(fb[0], b_ad[kk_], (s_) * 32768 + 0);             \
+    MLPHS_DSREAD(fb[1], b_ad[kk_], (s_) * 32768 + 4096);          \
+  } while (0)
+  // at most n_ LDS reads outstanding (they return in order); the fragments named become usable
+#define MLPHS_WAIT(n_, fa, fb)                                                                           \
+  asm volatile("s_waitcnt lgkmcnt(" #n_ ")"                                                              \
+               : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1]))
+#define MLPHS_MFMA(fa, fb)                                                                               \
+  do {                                                                                                   \
+    _Pragma("unroll") for (int i_ = 0; i_ < TM; ++i_)                                                    \
+        _Pragma("unroll") for (int j_ = 0; j_ < TN; ++j_)                                                \
+            acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i_]),    \
+                                                                 __builtin_bit_cast(bf16x8, fb[j_]), acc[i_][j_], 0, 0, 0); \
+  } while (0)
+  // LD_: request the slice after next into the stage just released; NX_: read the next slice's first fragments
+#define MLPHS_SLICE(s_, k2_, LD_, NX_)                                                                   \
+  do {                                                                                                   \
+    MLPHS_READ(qa, qb, s_, 1);                                                                           \
+    MLPHS_WAIT(6, pa, pb);                                                                               \
+    MLPHS_MFMA(pa, pb);                                                                                  \
+    MLPHS_READ(pa, pb, s_, 2);                                                                           \
+    MLPHS_WAIT(6, qa, qb);                                                                               \
+    MLPHS_MFMA(qa, qb);                                                                                  \
+    MLPHS_READ(qa, qb, s_, 3);                                                                           \
+    MLPHS_WAIT(6, pa, pb);                                                                               \
+    MLPHS_MFMA(pa, pb);                                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                                   \
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                     \
+    MLPHS_WAIT(0, qa, qb);                                                                               \
+    asm volatile("s_barrier" ::: "memory");                                                              \
+    if (LD_) MLPHS_FETCH(s_, (k2_) * 64);                                                                \
+    if (NX_) MLPHS_READ(pa, pb, (s_) ^ 1, 0);                                                            \
+    MLPHS_MFMA(qa, qb);                                                                                  \
+  } while (0)
+
+  const int nk = Kd / 64;                      // even and >= 2 (the launcher checks)
+  MLPHS_FETCH(0, 0);
+  MLPHS_FETCH(1, 64);
+  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");                 // slice 0 has landed, slice 1 may be in flight
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  u32x4 pa[4], pb[2], qa[4], qb[2];
+  MLPHS_READ(pa, pb, 0, 0);
+  int kt = 0;
+  for (; kt + 3 < nk; kt += 2) {               // steady state without branches
+    MLPHS_SLICE(0, kt + 2, 1, 1);
+    MLPHS_SLICE(1, kt + 3, 1, 1);
+  }
+  MLPHS_SLICE(0, 0, 0, 1);                     // slice nk-2: nothing left to request
+  MLPHS_SLICE(1, 0, 0, 0);                     // slice nk-1
+#undef MLPHS_SLICE
+#undef MLPHS_MFMA
+#undef MLPHS_WAIT
+#undef MLPHS_READ
+#undef MLPHS_DSREAD
+#undef MLPHS_FETCH
+
+  float bcol[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bcol[j] = EPI == 1 ? 0.f : p.bias[tile_n * BN + wn * 64 + j * 32 + l32];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int gm = tile_m * BM + wm * 128 + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+      if (gm >= M) continue;
+      const int src = p.rowidx[gm];
+      const float* brow = EPI == 1 ? p.bias + static_cast<size_t>(p.krow[src]) * p.N : p.bias;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int gn = tile_n * BN + wn * 64 + j * 32 + l32;
+        const float c = acc[i][j][v] + (EPI == 1 ? brow[gn] : bcol[j]);
+        if (EPI == 3) p.outf[static_cast<size_t>(src) * p.N + gn] = c;
+        else p.outb[static_cast<size_t>(gm) * p.N + gn] = to_bf16_bits(silu(c));
+      }
+    }
+  }
+}
+
+// true when kernel_hs can take the problem (otherwise the generic 256 x 256 kernel does)
+inline bool hs_applicable(const Args& a) { return a.Kdim >= 128 && (a.Kdim / BK) % 2 == 0; }
+
+template <int EPI, bool GATHER = false, int PM = 4, int PN = 8>
+hipError_t launch_hs(const Args& a, int Rmax, hipStream_t st) {
+  constexpr size_t shmem = 131072;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel_hs<EPI, GATHER, PM, PN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles_m = (Rmax + 255) / 256, tiles_n = a.N / 256;
+  const int patches = ((tiles_m + PM - 1) / PM) * ((tiles_n + PN - 1) / PN);
+  const int grid = (patches * PM * PN + 7) / 8 * 8;
+  hipLaunchKernelGGL((kernel_hs<EPI, GATHER, PM, PN>), dim3(grid), dim3(512), shmem, st, a);
+  return hipGetLastError();
+}
+
 }  // namespace mlpgemm

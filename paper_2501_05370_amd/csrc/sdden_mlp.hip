@@ -69,7 +69,8 @@ int launch_gemm(const mlpgemm::Args& a, int R, hipStream_t st, std::string& err)
   const int t128 = ((R + 127) / 128) * (a.N / 128);
   const int t64 = ((R + 63) / 64) * (a.N / 128);
   hipError_t e;
-  if (4 * t256 >= 3 * ((t256 + 255) / 256) * 256) e = mlpgemm::launch<256, 256, 2, 4, EPI, 2, GATHER>(a, R, st);
+  if (4 * t256 >= 3 * ((t256 + 255) / 256) * 256)
+    e = mlpgemm::hs_applicable(a) ? mlpgemm::launch_hs<EPI, GATHER>(a, R, st) : mlpgemm::launch<256, 256, 2, 4, EPI, 2, GATHER>(a, R, st);
   else if (t128 >= 512) e = mlpgemm::launch<128, 128, 2, 2, EPI, 2, GATHER>(a, R, st);
   else if (t64 > 256) e = mlpgemm::launch<64, 128, 2, 2, EPI, 2, GATHER>(a, R, st);
   else e = mlpgemm::launch<64, 128, 2, 2, EPI, 4, GATHER>(a, R, st);
