@@ -43,7 +43,7 @@ DESCRIPTIONS = {
 # HBM bytes per launch of the roofline kernel (fetched * 2.0 + written * 1.0 of the rocprofv3 FETCH_SIZE /
 # WRITE_SIZE counters, the factors being what the same counters read for a plain device copy), taken from
 # profiles/hbm_traffic_all_kernels_c4.md; workloads without such a counter run report null
-MEASURED_TRAFFIC_BYTES = {"c4": 1233.0e6}
+MEASURED_TRAFFIC_BYTES = {"c4": 1231.0e6}
 
 # published MI355X peaks used as roofline denominators
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "mfma_fp32": (157.3, "TFLOP/s"),
@@ -59,7 +59,7 @@ def roofline_plan(cfg):
         H = cfg.params.H
         # the batched evaluation of the drafted states (rows = sum Kt - chain-windows); the window-start
         # call (one row per chain, a smaller tile) is left out of this figure
-        return dict(kernel="mlpgemm::kernel<256,256,2,4,EPI=1,NS=2,GATHER> layer-1 GEMM of the batched target call, rows x 12288 -> 4096, "
+        return dict(kernel="mlpgemm::kernel_hs<EPI=1,GATHER> (256x256x64 tiles, 8 waves) layer-1 GEMM of the batched target call, rows x 12288 -> 4096, "
                            "bf16 MFMA, A rows gathered from the bf16 image of the drafts (largest share of the kernel time; layer 3 has the "
                            "same flops and runs within 5% of it)",
                     den_which=1, den_min_rows=cfg.B + 1, bound="mfma", peak="mfma_bf16", scale=1e-12,
