@@ -496,17 +496,23 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Advance + compaction.  One workgroup scans the batch in chunks of its size: dest <= source
-// always holds for a stable compaction to the front, and a chunk reads all its inputs before it
-// writes, so n and chain_id can be rewritten in place.  A second kernel moves the states.
+// Advance + compaction.  One workgroup scans the batch in passes of kScanChunks chunks of its own
+// size: all loads of a pass are issued together, each chunk's survivors are counted with a
+// wavefront ballot, one wavefront turns the (chunk, wavefront) totals into offsets, and the chunk
+// positions are written.  dest <= source always holds for a stable compaction to the front, and a
+// pass reads all its inputs before it writes, so n and chain_id can be rewritten in place.  Rows
+// between the device-side chain count and B get dest = -2 (the mover skips them).  A second kernel
+// moves the states.
 // ---------------------------------------------------------------------------------------------
 constexpr int kScanBlock = 1024;
+constexpr int kScanWaves = kScanBlock / 64;
+constexpr int kScanChunks = 16;             // chunks per pass: 16384 chains per three barriers
 
 __global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
     const int32_t* __restrict__ adv, const uint8_t* __restrict__ rej, int32_t* n, int64_t* chain_id,
     int32_t* __restrict__ dest, int64_t* __restrict__ outrow, int32_t* B_active, int64_t* counters,
     const int32_t* active, int B, int T, int K) {
-  __shared__ int wave_tot[kScanBlock / 64];
+  __shared__ int tot[kScanChunks * kScanWaves];          // survivors per (chunk, wavefront), then their offsets
   __shared__ int sh_base;
   __shared__ long long sh_cnt[3];
   const int Bact = active_chains(active, B);
@@ -514,49 +520,79 @@ __global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
   if (tid == 0) { sh_base = 0; sh_cnt[0] = sh_cnt[1] = sh_cnt[2] = 0; }
   __syncthreads();
   long long my_adv = 0, my_rej = 0, my_kt = 0;
-  for (int start = 0; start < Bact; start += kScanBlock) {
-    const int b = start + tid;
-    const bool in = b < Bact;
-    int nn = 0;
-    int64_t id = 0;
-    bool keep = false;
-    if (in) {
-      my_kt += min(K, T - n[b]);
-      nn = n[b] + adv[b];
-      id = chain_id[b];
-      keep = nn < T;
-      my_adv += adv[b];
-      if (rej) my_rej += rej[b];
+  for (int start = 0; start < Bact; start += kScanBlock * kScanChunks) {
+    int nn[kScanChunks], before[kScanChunks];
+    int64_t id[kScanChunks];
+    unsigned keep_bits = 0;
+#pragma unroll
+    for (int i = 0; i < kScanChunks; ++i) {
+      const int b = start + i * kScanBlock + tid;
+      nn[i] = 0; id[i] = 0;
+      bool keep = false;
+      if (b < Bact) {
+        const int n0 = n[b], a = adv[b];
+        my_kt += min(K, T - n0);
+        nn[i] = n0 + a;
+        id[i] = chain_id[b];
+        keep = nn[i] < T;
+        my_adv += a;
+        if (rej) my_rej += rej[b];
+      }
+      const unsigned long long m = __ballot(keep);
+      before[i] = __popcll(m & ((1ull << lane) - 1ull));
+      if (lane == 0) tot[i * kScanWaves + wave] = __popcll(m);
+      keep_bits |= keep ? 1u << i : 0u;
     }
-    const unsigned long long m = __ballot(keep);
-    const int before = __popcll(m & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_tot[wave] = __popcll(m);
     __syncthreads();
-    int offset = sh_base;
-    for (int w = 0; w < wave; ++w) offset += wave_tot[w];
-    if (in) {
-      if (keep) {
-        const int dpos = offset + before;
-        dest[b] = dpos;
-        n[dpos] = nn;
-        chain_id[dpos] = id;
-      } else {
-        dest[b] = -1;
-        outrow[b] = id;
+    const int base = sh_base;
+    if (wave == 0) {                                    // exclusive prefix over the 256 totals, four per lane
+      constexpr int PER = kScanChunks * kScanWaves / 64;
+      int v[PER], local = 0;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) { v[e] = tot[lane * PER + e]; local += v[e]; }
+      int incl = local;
+#pragma unroll
+      for (int s = 1; s < 64; s <<= 1) {
+        const int up = __shfl_up(incl, s, 64);
+        if (lane >= s) incl += up;
+      }
+      int run = incl - local;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) { tot[lane * PER + e] = run; run += v[e]; }
+      if (lane == 63) sh_base = base + incl;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kScanChunks; ++i) {
+      const int b = start + i * kScanBlock + tid;
+      if (b < Bact) {
+        if (keep_bits >> i & 1u) {
+          const int dpos = base + tot[i * kScanWaves + wave] + before[i];
+          dest[b] = dpos;
+          n[dpos] = nn[i];
+          chain_id[dpos] = id[i];
+        } else {
+          dest[b] = -1;
+          outrow[b] = id[i];
+        }
       }
     }
-    __syncthreads();
-    if (tid == 0) {
-      int tot = 0;
-      for (int w = 0; w < kScanBlock / 64; ++w) tot += wave_tot[w];
-      sh_base += tot;
-    }
-    __syncthreads();
+    __syncthreads();                                    // tot and sh_base are reused by the next pass
   }
+  for (int b = Bact + tid; b < B; b += kScanBlock) dest[b] = -2;
   if (counters) {
-    atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[0]), static_cast<unsigned long long>(my_adv));
-    atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[2]), static_cast<unsigned long long>(my_rej));
-    atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[1]), static_cast<unsigned long long>(my_kt));
+    // wavefront sums first: one LDS atomic per wavefront and counter, not one per thread
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) {
+      my_adv += __shfl_xor(my_adv, s, 64);
+      my_rej += __shfl_xor(my_rej, s, 64);
+      my_kt += __shfl_xor(my_kt, s, 64);
+    }
+    if (lane == 0) {
+      atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[0]), static_cast<unsigned long long>(my_adv));
+      atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[2]), static_cast<unsigned long long>(my_rej));
+      atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[1]), static_cast<unsigned long long>(my_kt));
+    }
   }
   __syncthreads();
   if (tid == 0) {
@@ -582,7 +618,7 @@ __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __res
                                                               float* __restrict__ carry_dst,
                                                               const int32_t* __restrict__ adv, int rs) {
   // Bprev = number of chains that entered the window (host bound; rows beyond the device-side
-  // count carry dest = -2 from the fill below and are skipped).
+  // count carry dest = -2 from the scan kernel and are skipped).
   const int b = blockIdx.x / chunks;
   const int chunk = blockIdx.x % chunks;
   if (b >= Bprev) return;
@@ -603,11 +639,6 @@ __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __res
       v.store(carry_dst + static_cast<int64_t>(dpos) * d + static_cast<int64_t>(col) * VEC);
     }
   }
-}
-
-__global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
 }
 
 int check_ctx(sd_ctx* ctx) { return ctx ? SD_OK : SD_ERR_ARG; }
@@ -845,9 +876,6 @@ int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, c
   hipStream_t st = static_cast<hipStream_t>(stream);
   int32_t* dest = static_cast<int32_t*>(ctx->ws);
   int64_t* outrow = reinterpret_cast<int64_t*>(static_cast<char*>(ctx->ws) + ((static_cast<size_t>(B) * 4 + 7) / 8) * 8);
-  if (B > 0 && ctx->active) {   // rows beyond the device-side count must be recognisable
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((B + 255) / 256), dim3(256), 0, st, dest, B, -2);
-  }
   hipLaunchKernelGGL(advance_scan_kernel, dim3(1), dim3(kScanBlock), 0, st, adv, rejected, n, chain_id,
                      dest, outrow, B_active, counters, ctx->active, B, ctx->T, ctx->K);
   if (B > 0) {

@@ -123,6 +123,89 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_kernel(
   }
 }
 
+// Small mixtures (MP = M rounded up to a power of two <= 32, d <= (64 / MP) * NI): a lane computes the
+// per-component posterior mean of its (component, coordinate) pairs in the same pass as the quadratic
+// form and keeps it in registers, so the reciprocal variance and x - sqrt(ab) mu are computed once
+// instead of once per phase.
+// Lane = (component m, part); the lane owns coordinates i = part + PARTS * j, j < NI.  Phase 1 sums
+// its quadratic form and finishes it across the parts; the softmax runs across the MP lanes of a
+// part; phase 2 scales the kept means by r_m and a
+// halving exchange over the component lanes leaves each lane with the finished sums of NI / MP
+// coordinates, which it writes.  No LDS, no barrier.
+template <int MP, int NI>
+__global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_reg_kernel(GmmArgs p) {
+  static_assert(NI % MP == 0 && MP <= 32 && (MP & (MP - 1)) == 0, "component lanes must divide the coordinate list");
+  constexpr int PARTS = 64 / MP;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = blockIdx.x * kRowsPerBlock + wave;
+  const int Ract = sdi::active_rows(p.active, p.rows_per_chain, p.R);
+  const int k = r < Ract ? p.krow[r] : -1;
+  if (k < 0) return;                        // whole wavefront leaves together
+  const double ab = p.ab[k];
+  const double sab = sqrt(ab), om = 1.0 - ab;
+  const int m = lane % MP, part = lane / MP;
+  const bool live = m < p.M;
+  const float* x = p.X + static_cast<int64_t>(r) * p.d;
+
+  double v[NI];                             // posterior mean of component m at the owned coordinates
+  double q = 0.0;
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int i = part + PARTS * j;
+    v[j] = 0.0;
+    if (live && i < p.d) {
+      const double mu = p.muT[static_cast<int64_t>(i) * p.M + m];
+      const double sd = p.sdT[static_cast<int64_t>(i) * p.M + m];
+      const double s2 = sd * sd;
+      const double iv = reciprocal(fma(ab, s2, om));
+      const double df = fma(-sab, mu, static_cast<double>(x[i]));
+      q = fma(df * df, iv, q);
+      v[j] = fma(sab * s2 * iv, df, mu);
+    }
+  }
+#pragma unroll
+  for (int s = MP; s < 64; s <<= 1) q += __shfl_xor(q, s, 64);
+  const double logit = live ? p.cst[static_cast<int64_t>(k) * p.M + m] - 0.5 * q : -INFINITY;
+  double mx = logit;
+#pragma unroll
+  for (int s = MP / 2; s >= 1; s >>= 1) mx = fmax(mx, __shfl_xor(mx, s, 64));
+  const double e = live ? exp(logit - mx) : 0.0;
+  double sum = e;
+#pragma unroll
+  for (int s = MP / 2; s >= 1; s >>= 1) sum += __shfl_xor(sum, s, 64);
+  const double rm = e / sum;
+#pragma unroll
+  for (int j = 0; j < NI; ++j) v[j] *= rm;
+  // halving exchange over the component lanes: at distance s a lane keeps the upper half of its list if its
+  // bit s is set (else the lower half) and receives the partner's sums for that half
+  int n = NI;
+#pragma unroll
+  for (int s = MP / 2; s >= 1; s >>= 1) {
+    const bool up = lane & s;
+    n >>= 1;
+#pragma unroll
+    for (int j = 0; j < NI / 2; ++j) {
+      if (j < n) {
+        const double send = up ? v[j] : v[j + n];
+        const double keep = up ? v[j + n] : v[j];
+        v[j] = keep + __shfl_xor(send, s, 64);
+      }
+    }
+  }
+  constexpr int C = NI / MP;                // finished coordinates per lane: j = m * C + jj
+  float* o = p.out + static_cast<int64_t>(r) * p.d;
+#pragma unroll
+  for (int jj = 0; jj < C; ++jj) {
+    const int i = part + PARTS * (m * C + jj);
+    if (i < p.d) o[i] = static_cast<float>(v[jj]);
+  }
+}
+
+template <int MP, int NI>
+void launch_reg(const GmmArgs& p, unsigned grid, hipStream_t st) {
+  hipLaunchKernelGGL((gmm_posterior_mean_reg_kernel<MP, NI>), dim3(grid), dim3(64 * kRowsPerBlock), 0, st, p);
+}
+
 struct GmmDenoiser final : sdden {
   int M = 0;
   float* dev_f = nullptr;     // mu, sd, muT, sdT, ab
@@ -142,8 +225,20 @@ struct GmmDenoiser final : sdden {
     p.R = R; p.d = d; p.M = M;
     const size_t shmem = sizeof(double) * kRowsPerBlock * static_cast<size_t>(M + d);
     const unsigned grid = static_cast<unsigned>((R + kRowsPerBlock - 1) / kRowsPerBlock);
+    constexpr int kRegNI = 32;               // coordinates per lane of the register-resident kernel
     prof.mark(1, st);
-    hipLaunchKernelGGL(gmm_posterior_mean_kernel, dim3(grid), dim3(64 * kRowsPerBlock), shmem, st, p);
+    if (p.Mp <= 32 && d <= (64 / p.Mp) * kRegNI) {
+      switch (p.Mp) {
+        case 32: launch_reg<32, kRegNI>(p, grid, st); break;
+        case 16: launch_reg<16, kRegNI>(p, grid, st); break;
+        case 8: launch_reg<8, kRegNI>(p, grid, st); break;
+        case 4: launch_reg<4, kRegNI>(p, grid, st); break;
+        case 2: launch_reg<2, kRegNI>(p, grid, st); break;
+        default: launch_reg<1, kRegNI>(p, grid, st); break;
+      }
+    } else {
+      hipLaunchKernelGGL(gmm_posterior_mean_kernel, dim3(grid), dim3(64 * kRowsPerBlock), shmem, st, p);
+    }
     prof.mark(1, st);
     SD_HIP_TRY(err, hipGetLastError());
     return SD_OK;
