@@ -619,15 +619,23 @@ __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __res
                                                               const int32_t* __restrict__ adv, int rs) {
   // Bprev = number of chains that entered the window (host bound; rows beyond the device-side
   // count carry dest = -2 from the scan kernel and are skipped).
-  const int b = blockIdx.x / chunks;
-  const int chunk = blockIdx.x % chunks;
+  // chunks > 0: a row takes `chunks` workgroups; chunks < 0: a workgroup takes -chunks whole rows
+  const int ncol = d / VEC;
+  int b, col;
+  if (chunks > 0) {
+    b = blockIdx.x / chunks;
+    col = (blockIdx.x % chunks) * kBlock + threadIdx.x;
+  } else {
+    const int rows = -chunks;
+    const int slot = threadIdx.x / ncol;
+    b = blockIdx.x * rows + slot;
+    col = slot < rows ? static_cast<int>(threadIdx.x) - slot * ncol : ncol;
+  }
   if (b >= Bprev) return;
   const int dpos = dest[b];
   if (dpos == -2) return;
   float* dst = dpos >= 0 ? y + static_cast<int64_t>(dpos) * d : out + outrow[b] * d;
   const float* src = y_out + static_cast<int64_t>(b) * d;
-  const int ncol = d / VEC;
-  const int col = chunk * kBlock + threadIdx.x;
   if (col < ncol) {
     Pack<VEC> v;
     v.load(src + static_cast<int64_t>(col) * VEC);
@@ -882,8 +890,11 @@ int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, c
     const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y_out) && sdi::aligned16(y) && sdi::aligned16(out) &&
                      sdi::aligned16(ctx->carry_src) && sdi::aligned16(ctx->carry_dst);
     const int ncol = vec ? ctx->d / 4 : ctx->d;
-    const int chunks = (ncol + kBlock - 1) / kBlock;
-    const int64_t grid = static_cast<int64_t>(B) * chunks;
+    // short rows share a workgroup (negative `chunks` = rows per workgroup), long rows are split over several
+    const int rows_per_wg = ncol <= kBlock / 2 ? kBlock / ncol : 1;
+    const int chunks = rows_per_wg > 1 ? -rows_per_wg : (ncol + kBlock - 1) / kBlock;
+    const int64_t grid = rows_per_wg > 1 ? (static_cast<int64_t>(B) + rows_per_wg - 1) / rows_per_wg
+                                         : static_cast<int64_t>(B) * chunks;
     if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_advance: B*d too large");
     const float* csrc = ctx->mode == SD_DRAFT_FROZEN_REUSED ? ctx->carry_src : nullptr;
     if (vec) hipLaunchKernelGGL(advance_move_kernel<4>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,

@@ -158,7 +158,8 @@ def test_verify_degenerate_cases():
                   y_out, adv, rej, None, None)
 
 
-@pytest.mark.parametrize("B,d", [(1, 2), (64, 2), (1500, 64), (3000, 5), (40, 1000)])
+# 16385 and 40000 chains: more than one pass of the scan (16 chunks of 1024 chains per pass)
+@pytest.mark.parametrize("B,d", [(1, 2), (64, 2), (1500, 64), (3000, 5), (40, 1000), (16385, 2), (40000, 4)])
 def test_advance_matches_oracle(B, d):
     rng = np.random.default_rng(4)
     T, K = 50, 6
