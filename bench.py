@@ -70,11 +70,13 @@ def roofline_plan(cfg):
                     den_min_rows=cfg.B + 1, bound="mfma", peak="mfma_fp32", scale=1e-12,
                     work=lambda c: 2.0 * (c[4] - c[1]) * d * rpad)
     if cfg.kind == "gmm":
-        # verify/reflect: pass 1 reads y, D0, Kt drafts, Kt-1 predictions; pass 2 re-reads 4 rows and
-        # writes 1 on a rejection, else copies 1 row
-        return dict(kernel="verify_kernel (accept / first-reject / reflect)", stage="verify",
-                    bound="hbm", peak="hbm", scale=1e-9,
-                    work=lambda c: 4.0 * d * ((2 * c[4] + c[1]) + 5 * c[2] + 2 * (c[1] - c[2])))
+        # the analytic denoiser bounds these windows (about 3/4 of the kernel time).  fp64 flops per
+        # (component, coordinate) pair: variance 3, reciprocal counted as 1, x - sqrt(ab) mu 2, quadratic form 3,
+        # gain 2, component mean 2, weighting and the sum over components 2
+        M = cfg.params.means.shape[0]
+        return dict(kernel="gmm_posterior_mean_reg_kernel (mixture posterior mean, fp64) of the batched target call", den_which=1,
+                    den_min_rows=cfg.B + 1, bound="alu", peak="alu_fp64", scale=1e-12,
+                    work=lambda c: 15.0 * M * d * (c[4] - c[1]))
     if cfg.kind == "langevin":
         M = cfg.params.means.shape[0]
         # fp64 flops per evaluated position: logits 3 M d, gradient 2 M d + 2 d, Delta / dots / update 12 d
