@@ -159,7 +159,9 @@ int sd_draft_step(sd_ctx* ctx, int32_t B, int32_t j, const float* prev, const in
  *      Dq [B,K,d], row j-1 = D(y~_{n+j-1}, n+j-1); Ytilde [B,K,d]                     (dev)
  * out: y_out [B,d]; adv [B] int32 in 1..Kt; rejected [B] uint8;
  *      logratio, logu [B,K] float or NULL: the log acceptance ratio (already divided by tau) and
- *      log u of every position j <= Kt (0 beyond), for diagnostics and parity checks.   (dev) */
+ *      log u of every position j <= Kt (0 beyond), for diagnostics and parity checks.   (dev)
+ *      With both NULL the rows of Ytilde and Dq that lie a whole group of 8 positions past the
+ *      chain's first rejection are not read (they decide nothing). */
 int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int64_t* chain_id,
               const float* D0_or_mp, const float* Dq, const float* Ytilde, float* y_out,
               int32_t* adv, uint8_t* rejected, float* logratio, float* logu, void* stream);

@@ -275,7 +275,8 @@ __global__ __launch_bounds__(kBlock) void draft_step_kernel(DraftStepArgs p) {
 // walks the window positions, keeping the previous row in registers, and accumulates the two
 // dot products of every position in fp64.  The per-position sums are reduced with wavefront
 // shuffles (and LDS across wavefronts), the first kJC lanes of the chain run the accept test of
-// one position each, and a ballot finds the first rejection.  Pass 2 re-reads only the
+// one position each, and a ballot finds the first rejection; the chunks of kJC positions after it
+// are not read (unless the per-position diagnostics are asked for).  Pass 2 re-reads only the
 // rejected row and writes the reflected state (or copies the last draft).
 //
 // All loop bounds depend on K only, so every barrier and shuffle is reached by all threads.
@@ -323,6 +324,7 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
   const int64_t winB = static_cast<int64_t>(b) * p.rs * p.d;     // offset of the chain's rows in Ytil, Dq
   const int64_t yoff = static_cast<int64_t>(p.roff) * p.d;       // first draft within the chain's rows of Ytil
   const bool skip0 = FROZEN && p.first_exact;
+  const bool need_all = p.logratio != nullptr || p.logu != nullptr;
 
   if (t == 0) sh_jr[slot] = -1;
   __syncthreads();
@@ -339,7 +341,9 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
 #pragma unroll
     for (int jj = 0; jj < kJC; ++jj) s1[jj] = s2[jj] = 0.0;
 
-    if (jc < Kt) {
+    // a chunk after the chain's first rejection decides nothing: it is streamed only when the caller asked
+    // for the per-position log-ratios (sh_jr was last written before the barrier that ended the previous chunk)
+    if (jc < Kt && (need_all || sh_jr[slot] < 0)) {
       for (int col = t; col < ncol; col += TPC) {
         const int64_t off = static_cast<int64_t>(col) * VEC;
         Pack<VEC> prev, d0;

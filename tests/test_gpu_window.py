@@ -127,11 +127,14 @@ def test_verify_matches_oracle(name, kw, mode, tau):
     assert rel_err(host(y_out)[same], res.y_out[same]) < TOL
     assert np.max(np.abs(host(lu) - res.logu)) < 1e-5
     assert np.max(np.abs(host(lr) - res.logratio) / np.maximum(1.0, np.abs(res.logratio))) < 1e-5
-    # without the diagnostic outputs the decisions are the same
+    # without the diagnostic outputs (groups of positions past the first rejection are then not read)
+    # the decisions and the states are the same, bit for bit
     adv2 = torch.zeros_like(adv)
+    y_out2 = torch.full_like(y_out, -3.0)
     ctx.sd_verify(B, f32(y), dev(n, torch.int32), dev(ids, torch.int64), f32(D0 if mp is None else mp),
-                  f32(Dq), f32(Ytil), y_out, adv2, None, None, None)
+                  f32(Dq), f32(Ytil), y_out2, adv2, None, None, None)
     assert np.array_equal(host(adv2), g_adv)
+    assert np.array_equal(host(y_out2), host(y_out))
 
 
 def test_verify_degenerate_cases():
