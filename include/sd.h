@@ -160,7 +160,7 @@ int sd_draft_step(sd_ctx* ctx, int32_t B, int32_t j, const float* prev, const in
  * out: y_out [B,d]; adv [B] int32 in 1..Kt; rejected [B] uint8;
  *      logratio, logu [B,K] float or NULL: the log acceptance ratio (already divided by tau) and
  *      log u of every position j <= Kt (0 beyond), for diagnostics and parity checks.   (dev)
- *      With both NULL the rows of Ytilde and Dq that lie a whole group of 8 positions past the
+ *      With both NULL the rows of Ytilde and Dq that lie a whole group of 4 positions past the
  *      chain's first rejection are not read (they decide nothing). */
 int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const int64_t* chain_id,
               const float* D0_or_mp, const float* Dq, const float* Ytilde, float* y_out,

@@ -14,7 +14,7 @@
 namespace {
 
 constexpr int kBlock = 256;   // threads per workgroup (4 wavefronts of 64)
-constexpr int kJC = 8;        // window positions reduced together in the verify kernel
+constexpr int kJC = 4;        // window positions reduced together in the verify kernel
 
 std::string g_create_error;
 
