@@ -47,7 +47,10 @@ MEASURED_TRAFFIC_BYTES = {"c4": 1231.0e6}
 
 # published MI355X peaks used as roofline denominators
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "mfma_fp32": (157.3, "TFLOP/s"),
-        "alu_fp64": (78.6, "TFLOP/s"), "alu_fp32": (157.3, "TFLOP/s")}
+        "alu_fp64": (78.6, "TFLOP/s"), "alu_fp32": (157.3, "TFLOP/s"),
+        # vector instruction issue: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (the fp32
+        # figure is this times 2 for the FMA and 2 for the packed form)
+        "alu_lane": (39.3, "T lane-op/s")}
 
 
 def roofline_plan(cfg):
@@ -84,11 +87,11 @@ def roofline_plan(cfg):
                     bound="alu", peak="alu_fp64", scale=1e-12,
                     work=lambda c: float(c[0] + c[1]) * d * (5.0 * M + 14.0))
     if cfg.kind == "phi4":
-        # lane operations per site and evaluated position: Philox + Box-Muller about 40 (int32 / fp32), the
-        # stencil gradient, Delta, the two dot products and the update about 30 in fp64 (counted twice:
-        # half-rate), against the fp32 vector peak
+        # lane instructions per site and evaluated position: Philox + Box-Muller about 40 (int32 / fp32), the
+        # stencil gradient, Delta, the two dot products and the update about 30 in fp64 (two issue slots each),
+        # against the vector issue rate
         return dict(kernel="phi4_window_kernel<16> (fused draft + stencil gradient + verify, 16 lanes per chain)",
-                    stage="langevin_window", bound="alu", peak="alu_fp32", scale=1e-12,
+                    stage="langevin_window", bound="alu", peak="alu_lane", scale=1e-12,
                     work=lambda c: float(c[0] + c[1]) * d * 100.0)
     raise ValueError(cfg.kind)
 
