@@ -192,7 +192,12 @@ def test_advance_matches_oracle(B, d):
 
 
 def test_gmm_denoiser_matches_oracle():
-    for name, kw in (("c1", dict(B=64)), ("c2", dict(B=64)), ("c2", dict(B=8, d=300, M=70))):
+    # c1, c2 and the small mixtures take the register-resident kernel at every lane split (1, 2, 4, 8, 16, 32
+    # component lanes; ragged d, M not a power of two); M = 70 and d = 1100 take the general kernel
+    for name, kw in (("c1", dict(B=64)), ("c2", dict(B=64)), ("c2", dict(B=8, d=300, M=70)),
+                     ("c2", dict(B=8, d=40, M=1)), ("c2", dict(B=8, d=100, M=2)), ("c2", dict(B=8, d=200, M=3)),
+                     ("c2", dict(B=8, d=17, M=5)), ("c2", dict(B=8, d=128, M=12)), ("c2", dict(B=8, d=30, M=32)),
+                     ("c2", dict(B=8, d=1024, M=2)), ("c2", dict(B=8, d=1100, M=2))):
         cfg, den = _gmm_case(name, **kw)
         from paper_2501_05370_amd.binding import Denoiser
         g = Denoiser.sdden_gmm_create(cfg.params.means, cfg.params.stds, cfg.params.logw,
