@@ -309,7 +309,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   const int Kt = max(0, min(p.K, p.T - n));
   const int64_t id = p.id[b];
   const double gamma = p.gamma, inv_s2 = p.inv_s2;
-  const double sq2g = sqrt(2.0 * gamma), sqg2 = sqrt(0.5 * gamma);
+  const double sq2g = sqrt(2.0 * gamma), sqg2 = sqrt(0.5 * gamma), inv_sqg2 = 1.0 / sqg2;
   const int my_m = lane >> 2;                              // component this lane holds after a reduction
   const double my_logw = my_m < M ? static_cast<double>(p.logw[my_m]) : 0.0;
   const double my_hn = sh_hn[my_m];
@@ -423,7 +423,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           if (own[c][e])                                   // target gradient = g0 + Delta / sqrt(gamma/2)
-            cur[c][e] = cur[c][e] - gamma * (g0[c][e] + dl[c][e] / sqg2) +
+            cur[c][e] = cur[c][e] - gamma * (g0[c][e] + dl[c][e] * inv_sqg2) +
                         sq2g * (static_cast<double>(z[c][e]) - 2.0 * coef * dl[c][e]);
       break;
     }
@@ -514,7 +514,7 @@ __global__ __launch_bounds__(256) void phi4_window_kernel(Phi4Args p) {
   const int Kt = valid ? max(0, min(p.K, p.T - n)) : 0;
   const int64_t id = valid ? p.id[b] : 0;
   const double gamma = p.gamma, beta2 = 2.0 * p.beta;
-  const double sq2g = sqrt(2.0 * gamma), sqg2 = sqrt(0.5 * gamma);
+  const double sq2g = sqrt(2.0 * gamma), sqg2 = sqrt(0.5 * gamma), inv_sqg2 = 1.0 / sqg2;
   double* xs = sh_x + static_cast<size_t>(slot) * d;
 
   bool own[4];
@@ -593,7 +593,7 @@ __global__ __launch_bounds__(256) void phi4_window_kernel(Phi4Args p) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           if (own[e])                                // target gradient = g0 + Delta / sqrt(gamma/2)
-            cur[e] = cur[e] - gamma * (g0[e] + dl[e] / sqg2) + sq2g * (static_cast<double>(z[e]) - 2.0 * coef * dl[e]);
+            cur[e] = cur[e] - gamma * (g0[e] + dl[e] * inv_sqg2) + sq2g * (static_cast<double>(z[e]) - 2.0 * coef * dl[e]);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
