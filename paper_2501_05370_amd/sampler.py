@@ -260,6 +260,9 @@ class EfficientFrozenSampler(_SamplerBase):
         b.Dq_ext = torch.zeros(B, K + 1, d, **f32)
         ctx.sd_set_draft_mode(SD_DRAFT_FROZEN_REUSED)
         ctx.sd_set_carry(b.Dq_ext, b.Dfz)
+        # bf16 image of the window rows for denoisers whose first GEMM reads bf16 (written by sd_draft)
+        self.mirror = (torch.zeros(B, K + 1, d, dtype=torch.int16, device="cuda")
+                       if getattr(den, "wants_bf16", False) else None)
 
     def start(self, chain_ids: torch.Tensor, reset_counters: bool = True) -> int:
         B = super().start(chain_ids, reset_counters)
@@ -270,10 +273,16 @@ class EfficientFrozenSampler(_SamplerBase):
     def window(self, B: int, diagnostics=None):
         b, ctx, d, K, t = self.buf, self.ctx, self.ctx.d, self.ctx.K, self.timer
         with t.stage("draft", B):
+            ctx.sd_set_draft_mirror(self.mirror)
             ctx.sd_draft(B, b.y, b.n, b.chain_id, b.Dfz, b.X_ext, b.krow_ext)
+            ctx.sd_set_draft_mirror(None)
         with t.stage("predict_drafts", B):
             self._den_rows(self.den, K + 1)
-            self.den.sdden_eval(B * (K + 1), b.X_ext.view(-1, d), b.krow_ext.view(-1), b.Dq_ext.view(-1, d))
+            if self.mirror is not None:
+                self.den.sdden_eval_mirror(B * (K + 1), b.X_ext.view(-1, d), self.mirror.view(-1, d),
+                                           b.krow_ext.view(-1), b.Dq_ext.view(-1, d))
+            else:
+                self.den.sdden_eval(B * (K + 1), b.X_ext.view(-1, d), b.krow_ext.view(-1), b.Dq_ext.view(-1, d))
         lr, lu = diagnostics if diagnostics is not None else (None, None)
         with t.stage("verify", B):
             ctx.sd_verify(B, b.y, b.n, b.chain_id, b.Dfz, b.Dq_ext, b.X_ext, b.y_out, b.adv, b.rejected, lr, lu)

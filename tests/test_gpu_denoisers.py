@@ -156,3 +156,37 @@ def test_c4_shaped_window_pipeline():
     same = adv == res.adv
     assert same.mean() > 0.5
     assert rel_err(host(b.y_out)[same], res.y_out[same]) < 2e-2
+
+
+def test_c4_shaped_efficient_frozen_window_uses_the_bf16_image():
+    """Efficient frozen drafter on the MLP chain: the draft kernel writes the K+1 window rows (start state
+    + drafts) both as fp32 and as a bf16 image, and the one batched target call gathers its rows from the
+    image.  Drafts at the fp32 tolerance, image = round-to-nearest-even of the fp32 rows, predictions at the
+    bf16 tolerance."""
+    from paper_2501_05370_amd.runner import make_sampler
+    cfg = W.make_config("c4", B=40, d=256, H=256, K=6, T=50)
+    den = MLPDenoiser(cfg.params)
+    rng = np.random.default_rng(7)
+    B, K, d, T = cfg.B, cfg.K, cfg.d, cfg.T
+    n = rng.integers(0, T, size=B); n[:4] = [T - 1, T - 2, 0, T - K]
+    y = as_f32_f64(rng.standard_normal((B, d)))
+    ids = np.arange(B, dtype=np.int64)
+    Dfz = as_f32_f64(den(y, n) + 0.1 * rng.standard_normal((B, d)))
+    res, Ytil, Dq_ext, krow_ext, Dnext = S.window_efficient(cfg.schedule, den, y, n, ids, Dfz, K, cfg.seed)
+    smp = make_sampler(cfg, drafter="efficient_frozen")
+    assert smp.mirror is not None
+    b = smp.buf
+    b.y.copy_(f32(y)); b.n.copy_(dev(n, torch.int32)); b.chain_id.copy_(dev(ids, torch.int64)); b.Dfz.copy_(f32(Dfz))
+    smp.window(B)
+    X = host(b.X_ext)
+    assert np.array_equal(X[:, 0], y.astype(np.float32))
+    assert rel_err(X[:, 1:], Ytil) < 1e-5
+    assert np.array_equal(host(b.krow_ext), krow_ext)
+    img = smp.mirror.view(torch.bfloat16).float().cpu().numpy()
+    want = torch.from_numpy(X).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(img, want)
+    ev = krow_ext >= 0
+    assert rel_err(host(b.Dq_ext)[ev], Dq_ext[ev]) < 2e-2
+    adv = host(b.adv)
+    Kt = np.minimum(K, T - n)
+    assert np.all(adv >= 1) and np.all(adv <= Kt)
