@@ -163,3 +163,47 @@ def test_c5_full_size_sampled_chains():
     same = gadv == adv
     assert np.array_equal(host(b.rejected[sel])[same].astype(bool), rej[same])
     assert rel_err(host(b.y_out[sel])[same], xo[same]) < 1e-5
+
+
+def test_phi4_full_size_sampled_chains():
+    """The phi^4 lattice window at the benchmark's size (16384 chains of 8 x 8 sites, K = 20) in the launch
+    configuration bench.py times; sampled chains against the oracle's window on the same states."""
+    from oracle.langevin import Phi4Energy
+    from paper_2501_05370_amd.runner import make_sampler
+    cfg = W.make_config("phi4")
+    rng = np.random.default_rng(60)
+    B, d, K, T = cfg.B, cfg.d, cfg.K, cfg.T
+    Lside = cfg.params.L
+    y = (rng.choice([-1.0, 1.0], size=(B, 1)) + 0.15 * rng.standard_normal((B, d))).astype(np.float32)
+    n = rng.integers(0, T, size=B).astype(np.int64)
+    n[:16] = T - 1 - np.arange(16)
+    ids = np.arange(B, dtype=np.int64)
+    smp = make_sampler(cfg)
+    b = smp.buf
+    b.y.copy_(torch.from_numpy(y)); b.n.copy_(dev(n, torch.int32)); b.chain_id.copy_(dev(ids, torch.int64))
+    smp.window(B)
+    torch.cuda.synchronize()
+    sample = np.concatenate([np.arange(16), rng.choice(np.arange(16, B), 112, replace=False)])
+    xo, adv, rej, olr, olu = L.ula_window(Phi4Energy(Lside, cfg.params.beta), y[sample].astype(np.float64), n[sample],
+                                          ids[sample], K, T, cfg.gamma, seed=cfg.seed)
+    sel = torch.as_tensor(sample, device="cuda")
+
+    class R:
+        pass
+    R.adv, R.logu, R.logratio = adv, olu, olr
+    gadv = host(b.adv[sel])
+    nbad, near = decisions_match(gadv, R)
+    print(f"[phi4 full size] sampled {len(sample)} of {B} chains: mean adv {adv.mean():.2f}, rejected {rej.mean():.2f}, "
+          f"mismatches {nbad} (near ties {near})")
+    assert nbad == near
+    same = gadv == adv
+    assert same.mean() > 0.9
+    assert np.array_equal(host(b.rejected[sel])[same].astype(bool), rej[same])
+    assert rel_err(host(b.y_out[sel])[same], xo[same]) < 1e-5
+    # advance at this size: the scan's single pass of 16 chunks
+    n_next = n + host(b.adv).astype(np.int64)
+    smp.advance(B)
+    Ba = int(host(b.B_active)[0])
+    assert Ba == int((n_next < T).sum())
+    assert np.array_equal(host(b.n)[:Ba], n_next[n_next < T])
+    assert np.array_equal(host(b.chain_id)[:Ba], ids[n_next < T])
