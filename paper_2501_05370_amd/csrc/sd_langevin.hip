@@ -390,14 +390,15 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   float z[CPT][4];
   for (int j = 0; j < Kt; ++j) {                           // Kt is uniform over the wavefront
     const uint32_t k1 = static_cast<uint32_t>(n + j + 1);
+    double lr = 0.0;
+    bool reject = false;
+    if (j > 0) gradient(dl);                               // position 1: the target gradient IS g0
+    // the noise and the uniform are drawn after the gradient, which is the register-hungry part
 #pragma unroll
     for (int c = 0; c < CPT; ++c)
       sdrng::normal4(p.seed, id, k1, sdrng::kStreamNoise, static_cast<uint32_t>(lane + 64 * c), z[c]);
-    double lr = 0.0;
     const double lu = sdrng::log_uniform(p.seed, id, k1);
-    bool reject = false;
-    if (j > 0) {                                           // position 1: the target gradient IS g0
-      gradient(dl);
+    if (j > 0) {
       double a1 = 0.0, a2 = 0.0;
 #pragma unroll
       for (int c = 0; c < CPT; ++c)
