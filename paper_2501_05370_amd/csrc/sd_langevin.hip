@@ -384,6 +384,10 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   double g0[CPT][4];
   gradient(g0);
 
+  // log u of the window's positions: lane j draws position j + 1 (the window has at most 64), once per
+  // window; a draw per position would cost every lane a Philox block and an fp64 log each time
+  const double lu_mine = lane < Kt ? sdrng::log_uniform(p.seed, id, static_cast<uint32_t>(n + lane + 1)) : 0.0;
+
   int jr = -1;
   double coef = 0.0;
   double dl[CPT][4];                                       // gradient at the draft, then Delta
@@ -397,7 +401,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
 #pragma unroll
     for (int c = 0; c < CPT; ++c)
       sdrng::normal4(p.seed, id, k1, sdrng::kStreamNoise, static_cast<uint32_t>(lane + 64 * c), z[c]);
-    const double lu = sdrng::log_uniform(p.seed, id, k1);
+    const double lu = readlane_f64(lu_mine, j);
     if (j > 0) {
       double a1 = 0.0, a2 = 0.0;
 #pragma unroll
@@ -560,13 +564,15 @@ __global__ __launch_bounds__(256) void phi4_window_kernel(Phi4Args p) {
   gradient(g0);
 
   int jr = -1;
+  double lu_batch = 0.0;                             // log u of position (j - j % G) + gl + 1, drawn G positions at a time
   for (int j = 0; j < p.K; ++j) {
     const bool alive = valid && j < Kt && jr < 0;
     if (__ballot(alive) == 0ull) break;              // uniform over the wavefront
     const uint32_t k1 = static_cast<uint32_t>(n + j + 1);
     float z[4];
     sdrng::normal4(p.seed, id, k1, sdrng::kStreamNoise, static_cast<uint32_t>(gl), z);
-    const double lu = sdrng::log_uniform(p.seed, id, k1);
+    if (j % G == 0) lu_batch = sdrng::log_uniform(p.seed, id, static_cast<uint32_t>(n + j + gl + 1));   // j is uniform
+    const double lu = __shfl(lu_batch, sub * G + j % G, 64);
     double lr = 0.0, coef = 0.0;
     bool reject = false;
     double dl[4] = {0.0, 0.0, 0.0, 0.0};
