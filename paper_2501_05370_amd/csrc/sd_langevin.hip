@@ -363,6 +363,10 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
 #pragma unroll
     for (int m = 0; m < kWaveM; ++m) {
       const double r = readlane_f64(r_mine, 4 * m);        // uniform: lives in scalar registers
+      // a component whose responsibility is below 1e-25 moves no coordinate of the weighted mean by more
+      // than 1e-25 |mu|, far below the last bit of anything downstream: its pass over the means is skipped
+      // (uniform branch).  Well-separated mixtures leave one or two components per state.
+      if (r < 1e-25) continue;
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
         const int g4 = lane + 64 * c;
