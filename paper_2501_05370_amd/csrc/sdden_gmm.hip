@@ -120,6 +120,7 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_kernel(
     const double xi = xs[i];
     double acc = 0.0;
     for (int m = 0; m < p.M; ++m) {
+      if (rs[m] < 1e-25) continue;          // the same for every lane; such a component moves nothing
       const double mu = p.mu[static_cast<int64_t>(m) * p.d + i];
       const double sd = p.sd[static_cast<int64_t>(m) * p.d + i];
       const double s2 = sd * sd;
