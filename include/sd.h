@@ -112,7 +112,8 @@ int sd_set_draft_mirror(sd_ctx* ctx, uint16_t* Ytilde_bf16);
  * NULL (default) restores row 0 of Dq. */
 int sd_set_start_prediction(sd_ctx* ctx, const float* D_start);
 
-/* Scratch for sd_advance (compaction map): bytes needed for batches up to Bmax, and the buffer. */
+/* Scratch for sd_advance (parked ids and steps, ranks, per-workgroup survivor counts: 16 bytes per chain
+ * plus 4 per 1024 chains): bytes needed for batches up to Bmax, and the buffer (8-byte aligned). */
 size_t sd_workspace_bytes(const sd_ctx* ctx, int32_t Bmax);
 int sd_set_workspace(sd_ctx* ctx, void* workspace /*dev*/, size_t bytes);
 

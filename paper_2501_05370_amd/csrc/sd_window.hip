@@ -500,92 +500,59 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Advance + compaction.  One workgroup scans the batch in passes of kScanChunks chunks of its own
-// size: all loads of a pass are issued together, each chunk's survivors are counted with a
-// wavefront ballot, one wavefront turns the (chunk, wavefront) totals into offsets, and the chunk
-// positions are written.  dest <= source always holds for a stable compaction to the front, and a
-// pass reads all its inputs before it writes, so n and chain_id can be rewritten in place.  Rows
-// between the device-side chain count and B get dest = -2 (the mover skips them).  A second kernel
-// moves the states.
+// Advance + compaction, in two launches with no wait between workgroups.
+// advance_rank_kernel: one workgroup per 1024 chains.  A chain that goes on gets its rank among the
+// survivors of its own workgroup (wavefront ballots + a prefix over the 16 wavefront totals); every
+// chain's new step and id are parked in the workspace (so that n and chain_id can be rewritten in place
+// afterwards), the workgroup's survivor count goes to totals[workgroup], the statistics to the counters.
+// advance_move_kernel: a chain's destination is the sum of the totals of the workgroups before its own
+// plus its rank (a stable compaction to the front); it moves the state row (and the carried prediction)
+// and rewrites n and chain_id.  Rows between the device-side chain count and B get rank -2 and are
+// skipped; workgroup 0 writes the new chain count.
 // ---------------------------------------------------------------------------------------------
 constexpr int kScanBlock = 1024;
 constexpr int kScanWaves = kScanBlock / 64;
-constexpr int kScanChunks = 16;             // chunks per pass: 16384 chains per three barriers
 
-__global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
-    const int32_t* __restrict__ adv, const uint8_t* __restrict__ rej, int32_t* n, int64_t* chain_id,
-    int32_t* __restrict__ dest, int64_t* __restrict__ outrow, int32_t* B_active, int64_t* counters,
-    const int32_t* active, int B, int T, int K) {
-  __shared__ int tot[kScanChunks * kScanWaves];          // survivors per (chunk, wavefront), then their offsets
-  __shared__ int sh_base;
+__global__ __launch_bounds__(kScanBlock) void advance_rank_kernel(
+    const int32_t* __restrict__ adv, const uint8_t* __restrict__ rej, const int32_t* __restrict__ n,
+    const int64_t* __restrict__ chain_id, int32_t* __restrict__ rank, int32_t* __restrict__ n_new,
+    int64_t* __restrict__ id_all, int32_t* __restrict__ totals, int64_t* counters, const int32_t* active, int B,
+    int T, int K) {
+  __shared__ int wave_tot[kScanWaves];
   __shared__ long long sh_cnt[3];
   const int Bact = active_chains(active, B);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) { sh_base = 0; sh_cnt[0] = sh_cnt[1] = sh_cnt[2] = 0; }
-  __syncthreads();
+  const int b = blockIdx.x * kScanBlock + tid;
+  if (tid == 0) sh_cnt[0] = sh_cnt[1] = sh_cnt[2] = 0;
+  const bool in = b < Bact;
+  int nn = 0;
   long long my_adv = 0, my_rej = 0, my_kt = 0;
-  for (int start = 0; start < Bact; start += kScanBlock * kScanChunks) {
-    int nn[kScanChunks], before[kScanChunks];
-    int64_t id[kScanChunks];
-    unsigned keep_bits = 0;
-#pragma unroll
-    for (int i = 0; i < kScanChunks; ++i) {
-      const int b = start + i * kScanBlock + tid;
-      nn[i] = 0; id[i] = 0;
-      bool keep = false;
-      if (b < Bact) {
-        const int n0 = n[b], a = adv[b];
-        my_kt += min(K, T - n0);
-        nn[i] = n0 + a;
-        id[i] = chain_id[b];
-        keep = nn[i] < T;
-        my_adv += a;
-        if (rej) my_rej += rej[b];
-      }
-      const unsigned long long m = __ballot(keep);
-      before[i] = __popcll(m & ((1ull << lane) - 1ull));
-      if (lane == 0) tot[i * kScanWaves + wave] = __popcll(m);
-      keep_bits |= keep ? 1u << i : 0u;
-    }
-    __syncthreads();
-    const int base = sh_base;
-    if (wave == 0) {                                    // exclusive prefix over the 256 totals, four per lane
-      constexpr int PER = kScanChunks * kScanWaves / 64;
-      int v[PER], local = 0;
-#pragma unroll
-      for (int e = 0; e < PER; ++e) { v[e] = tot[lane * PER + e]; local += v[e]; }
-      int incl = local;
-#pragma unroll
-      for (int s = 1; s < 64; s <<= 1) {
-        const int up = __shfl_up(incl, s, 64);
-        if (lane >= s) incl += up;
-      }
-      int run = incl - local;
-#pragma unroll
-      for (int e = 0; e < PER; ++e) { tot[lane * PER + e] = run; run += v[e]; }
-      if (lane == 63) sh_base = base + incl;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kScanChunks; ++i) {
-      const int b = start + i * kScanBlock + tid;
-      if (b < Bact) {
-        if (keep_bits >> i & 1u) {
-          const int dpos = base + tot[i * kScanWaves + wave] + before[i];
-          dest[b] = dpos;
-          n[dpos] = nn[i];
-          chain_id[dpos] = id[i];
-        } else {
-          dest[b] = -1;
-          outrow[b] = id[i];
-        }
-      }
-    }
-    __syncthreads();                                    // tot and sh_base are reused by the next pass
+  bool keep = false;
+  if (in) {
+    const int n0 = n[b], a = adv[b];
+    nn = n0 + a;
+    keep = nn < T;
+    my_kt = min(K, T - n0);
+    my_adv = a;
+    if (rej) my_rej = rej[b];
+    n_new[b] = nn;
+    id_all[b] = chain_id[b];
   }
-  for (int b = Bact + tid; b < B; b += kScanBlock) dest[b] = -2;
+  const unsigned long long m = __ballot(keep);
+  const int before = __popcll(m & ((1ull << lane) - 1ull));
+  if (lane == 0) wave_tot[wave] = __popcll(m);
+  __syncthreads();
+  int offset = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kScanWaves; ++w) {
+    const int c = wave_tot[w];
+    offset += w < wave ? c : 0;
+    total += c;
+  }
+  if (b < B) rank[b] = keep ? offset + before : (in ? -1 : -2);
+  if (tid == 0) totals[blockIdx.x] = total;
   if (counters) {
-    // wavefront sums first: one LDS atomic per wavefront and counter, not one per thread
+    // wavefront sums first: one LDS atomic per wavefront and counter, one global atomic per workgroup
 #pragma unroll
     for (int s = 32; s >= 1; s >>= 1) {
       my_adv += __shfl_xor(my_adv, s, 64);
@@ -597,33 +564,43 @@ __global__ __launch_bounds__(kScanBlock) void advance_scan_kernel(
       atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[2]), static_cast<unsigned long long>(my_rej));
       atomicAdd(reinterpret_cast<unsigned long long*>(&sh_cnt[1]), static_cast<unsigned long long>(my_kt));
     }
-  }
-  __syncthreads();
-  if (tid == 0) {
-    *B_active = sh_base;
-    if (counters) {
-      counters[0] += sh_cnt[0];
-      counters[1] += Bact;
-      counters[2] += sh_cnt[2];
-      counters[3] += Bact > 0 ? 1 : 0;
-      counters[4] += sh_cnt[1];
+    __syncthreads();
+    if (tid == 0) {
+      unsigned long long* c = reinterpret_cast<unsigned long long*>(counters);
+      if (sh_cnt[0]) atomicAdd(c + 0, static_cast<unsigned long long>(sh_cnt[0]));
+      if (sh_cnt[2]) atomicAdd(c + 2, static_cast<unsigned long long>(sh_cnt[2]));
+      if (sh_cnt[1]) atomicAdd(c + 4, static_cast<unsigned long long>(sh_cnt[1]));
+      if (blockIdx.x == 0) {
+        atomicAdd(c + 1, static_cast<unsigned long long>(Bact));
+        atomicAdd(c + 3, Bact > 0 ? 1ull : 0ull);
+      }
     }
   }
 }
 
+__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
+
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __restrict__ y_out,
-                                                              const int32_t* __restrict__ dest,
-                                                              const int64_t* __restrict__ outrow,
-                                                              float* __restrict__ y,
-                                                              float* __restrict__ out, int Bprev,
-                                                              int d, int chunks,
+                                                              const int32_t* __restrict__ rank,
+                                                              const int32_t* __restrict__ n_new,
+                                                              const int64_t* __restrict__ id_all,
+                                                              const int32_t* __restrict__ totals, float* __restrict__ y,
+                                                              int32_t* __restrict__ n, int64_t* __restrict__ chain_id,
+                                                              float* __restrict__ out, int32_t* __restrict__ B_active,
+                                                              int Bprev, int d, int chunks,
                                                               const float* __restrict__ carry_src,
                                                               float* __restrict__ carry_dst,
                                                               const int32_t* __restrict__ adv, int rs) {
-  // Bprev = number of chains that entered the window (host bound; rows beyond the device-side
-  // count carry dest = -2 from the scan kernel and are skipped).
-  // chunks > 0: a row takes `chunks` workgroups; chunks < 0: a workgroup takes -chunks whole rows
+  // Bprev = number of chains that entered the window (host bound; rows beyond the device-side count carry
+  // rank -2 and are skipped).  chunks > 0: a row takes `chunks` workgroups; chunks < 0: a workgroup takes
+  // -chunks whole rows.
+  const int nwg = (Bprev + kScanBlock - 1) / kScanBlock;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    int tot = 0;
+    for (int w = 0; w < nwg; ++w) tot += totals[w];
+    *B_active = tot;
+  }
   const int ncol = d / VEC;
   int b, col;
   if (chunks > 0) {
@@ -636,9 +613,20 @@ __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __res
     col = slot < rows ? static_cast<int>(threadIdx.x) - slot * ncol : ncol;
   }
   if (b >= Bprev) return;
-  const int dpos = dest[b];
-  if (dpos == -2) return;
-  float* dst = dpos >= 0 ? y + static_cast<int64_t>(dpos) * d : out + outrow[b] * d;
+  const int r = rank[b];
+  if (r == -2) return;
+  int dpos = -1;
+  if (r >= 0) {
+    dpos = r;
+    const int wg = b / kScanBlock;
+    for (int w = 0; w < wg; ++w) dpos += totals[w];
+  }
+  const int64_t id = id_all[b];
+  if (dpos >= 0 && (chunks > 0 ? blockIdx.x % chunks == 0 && threadIdx.x == 0 : col == 0)) {
+    n[dpos] = n_new[b];
+    chain_id[dpos] = id;
+  }
+  float* dst = dpos >= 0 ? y + static_cast<int64_t>(dpos) * d : out + id * d;
   const float* src = y_out + static_cast<int64_t>(b) * d;
   if (col < ncol) {
     Pack<VEC> v;
@@ -761,9 +749,9 @@ int sd_set_active_count(sd_ctx* ctx, const int32_t* count) {
 
 size_t sd_workspace_bytes(const sd_ctx* ctx, int32_t Bmax) {
   if (!ctx || Bmax <= 0) return 0;
-  // dest int32[B] (padded to 8 bytes) + outrow int64[B]
+  // ids int64[B], then rank int32[B], new steps int32[B], survivor totals int32[one per 1024 chains]
   const size_t b = static_cast<size_t>(Bmax);
-  return ((b * 4 + 7) / 8) * 8 + b * 8;
+  return b * 8 + b * 4 + b * 4 + ((b + kScanBlock - 1) / kScanBlock) * 4;
 }
 
 int sd_set_workspace(sd_ctx* ctx, void* workspace, size_t bytes) {
@@ -886,11 +874,19 @@ int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, c
     return sdi::fail(ctx->err, SD_ERR_WORKSPACE, "sd_advance: workspace of %zu bytes needed for B=%d, have %zu",
                      sd_workspace_bytes(ctx, B), B, ctx->ws_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  int32_t* dest = static_cast<int32_t*>(ctx->ws);
-  int64_t* outrow = reinterpret_cast<int64_t*>(static_cast<char*>(ctx->ws) + ((static_cast<size_t>(B) * 4 + 7) / 8) * 8);
-  hipLaunchKernelGGL(advance_scan_kernel, dim3(1), dim3(kScanBlock), 0, st, adv, rejected, n, chain_id,
-                     dest, outrow, B_active, counters, ctx->active, B, ctx->T, ctx->K);
-  if (B > 0) {
+  if (B == 0) {
+    hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, st, B_active, 0);
+    SD_HIP_TRY(ctx->err, hipGetLastError());
+    return SD_OK;
+  }
+  int64_t* id_all = static_cast<int64_t*>(ctx->ws);
+  int32_t* rank = reinterpret_cast<int32_t*>(id_all + B);
+  int32_t* n_new = rank + B;
+  int32_t* totals = n_new + B;
+  const int nwg = (B + kScanBlock - 1) / kScanBlock;
+  hipLaunchKernelGGL(advance_rank_kernel, dim3(nwg), dim3(kScanBlock), 0, st, adv, rejected, n, chain_id, rank, n_new,
+                     id_all, totals, counters, ctx->active, B, ctx->T, ctx->K);
+  {
     const bool vec = (ctx->d % 4 == 0) && sdi::aligned16(y_out) && sdi::aligned16(y) && sdi::aligned16(out) &&
                      sdi::aligned16(ctx->carry_src) && sdi::aligned16(ctx->carry_dst);
     const int ncol = vec ? ctx->d / 4 : ctx->d;
@@ -902,9 +898,11 @@ int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, c
     if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_advance: B*d too large");
     const float* csrc = ctx->mode == SD_DRAFT_FROZEN_REUSED ? ctx->carry_src : nullptr;
     if (vec) hipLaunchKernelGGL(advance_move_kernel<4>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
-                                y_out, dest, outrow, y, out, B, ctx->d, chunks, csrc, ctx->carry_dst, adv, ctx->K + 1);
+                                y_out, rank, n_new, id_all, totals, y, n, chain_id, out, B_active, B, ctx->d, chunks,
+                                csrc, ctx->carry_dst, adv, ctx->K + 1);
     else     hipLaunchKernelGGL(advance_move_kernel<1>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
-                                y_out, dest, outrow, y, out, B, ctx->d, chunks, csrc, ctx->carry_dst, adv, ctx->K + 1);
+                                y_out, rank, n_new, id_all, totals, y, n, chain_id, out, B_active, B, ctx->d, chunks,
+                                csrc, ctx->carry_dst, adv, ctx->K + 1);
   }
   SD_HIP_TRY(ctx->err, hipGetLastError());
   return SD_OK;

@@ -58,7 +58,7 @@ def test_create_validates_schedule_before_using_the_device():
     assert rc in (0, -4)                                    # -4 (SD_ERR_HIP) where there is no GPU
     if rc == 0:
         assert lib.sd_set_temperature(h, 0.0) == -1 and lib.sd_set_draft_mode(h, 7) == -1
-        assert lib.sd_workspace_bytes(h, 10) == 40 + 80
+        assert lib.sd_workspace_bytes(h, 10) == 10 * 16 + 4 and lib.sd_workspace_bytes(h, 1025) == 1025 * 16 + 8
         lib.sd_destroy(h)
 
 
