@@ -234,6 +234,12 @@ hipError_t launch(const Args& a, int Rmax, hipStream_t st) {
 //  * the workgroup barrier sits before the MFMAs of the slice's last k-step (all fragment reads of
 //    the stage have returned by then), so those MFMAs cover the issue of the next global loads and
 //    the first fragment reads of the next slice.
+// A hazard of this style: to the compiler an inline-asm read has completed when the statement ends, so it
+// is free to copy a fragment register (a PHI at the loop's back-edge, a merge after a branch) while the
+// data is still on its way.  The loop below carries its fragments in the registers the reads wrote (no
+// branch between a read and its wait; checked in the generated code: no move of a fragment register);
+// after a change of the loop structure or of the compiler the parity tests of the MLP denoiser are the
+// check -- a copied in-flight register shows up as errors of order one, not of rounding size.
 // ---------------------------------------------------------------------------------------------
 template <int EPI, bool GATHER = false, int PM = 4, int PN = 8>
 __global__ __launch_bounds__(512) void kernel_hs(Args p) {
