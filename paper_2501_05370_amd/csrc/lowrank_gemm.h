@@ -122,6 +122,42 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   for (int k = 0; k < NS - 1; ++k)
     if (k < nk) LRGEMM_FETCH(k, k);
 
+  // STAGE 2: everything the epilogue needs from memory is requested here, while the first slices are on
+  // their way: the tile's source rows and per-row scalars go through LDS (one row per thread), then each
+  // thread requests its 64 elements of X.  Left to the epilogue, the chain rowidx -> krow -> gperp -> X
+  // costs four dependent round trips per 32-row group, as much as the short K loop (K = rank) itself.
+  __shared__ int sh_src[STAGE == 2 ? BM : 1];
+  __shared__ float sh_gp[STAGE == 2 ? BM : 1], sh_cf[STAGE == 2 ? BM : 1];
+  float xv[STAGE == 2 ? TM : 1][16][TN];
+  float muv[TN];
+  if (STAGE == 2) {
+    if (t < BM) {
+      const int gm = tile_m * BM + t;
+      const int src = p.rowidx[gm < M ? gm : M - 1];
+      const int k = p.krow[src];
+      sh_src[t] = gm < M ? src : -1;
+      sh_gp[t] = p.gperp[k];
+      sh_cf[t] = p.coef[k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
+      muv[j] = gn < p.N ? p.mu[gn] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int src = sh_src[wm * (BM / WM) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3)];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
+          xv[i][v][j] = (src >= 0 && gn < p.N) ? p.X[static_cast<int64_t>(src) * p.N + gn] : 0.f;
+        }
+      }
+  }
+
   const int a_row = (wm * (BM / WM) + l32) * 128, b_row = (wn * (BN / WN) + l32) * 128;
   const int sw = l32 & 7;
   for (int kt = 0; kt < nk; ++kt) {
@@ -175,42 +211,20 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
     }
   }
   if (STAGE == 2) {
-    // all loads of a 32-row group are issued before its stores: X and out may alias as far as the
-    // compiler knows, and a load behind every store would serialise on the memory latency
-    float muv[TN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
-      muv[j] = gn < p.N ? p.mu[gn] : 0.f;
-    }
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      int64_t rowoff[16];
-      float gp[16], cf[16], xv[16][TN];
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int gm = tile_m * BM + wm * (BM / WM) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-        const int src = p.rowidx[gm < M ? gm : M - 1];
-        const int k = p.krow[src];
-        rowoff[v] = gm < M ? static_cast<int64_t>(src) * p.N : -1;
-        gp[v] = p.gperp[k];
-        cf[v] = p.coef[k];
+        const int row = wm * (BM / WM) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+        const int src = sh_src[row];
+        if (src < 0) continue;
+        const float gp = sh_gp[row], cf = sh_cf[row];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
+          if (gn < p.N) p.out[static_cast<int64_t>(src) * p.N + gn] = acc[i][j][v] + gp * xv[i][v][j] + cf * muv[j];
+        }
       }
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
-          xv[v][j] = (rowoff[v] >= 0 && gn < p.N) ? p.X[rowoff[v] + gn] : 0.f;
-        }
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
-          if (rowoff[v] >= 0 && gn < p.N) p.out[rowoff[v] + gn] = acc[i][j][v] + gp[v] * xv[v][j] + cf[v] * muv[j];
-        }
-    }
   }
 }
 
