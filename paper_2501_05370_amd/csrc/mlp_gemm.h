@@ -274,6 +274,17 @@ __global__ __launch_bounds__(512) void kernel_hs(Args p) {
     a_src[i] = reinterpret_cast<const unsigned char*>(p.A) + static_cast<size_t>(r) * Kd * 2 + 16 * lchunk;
   }
 
+  // the epilogue's row bookkeeping (dense row -> source row -> chain step) is fetched now, one row per thread,
+  // and parked in LDS: after the K loop it would be two dependent round trips ahead of the bias loads, with
+  // nothing else on the CU to hide them (the barriers of the K loop order these writes before the reads)
+  __shared__ int sh_src[BM], sh_step[BM];
+  if (t < BM) {
+    const int gm = tile_m * BM + t;
+    const int src = p.rowidx[gm < M ? gm : M - 1];
+    sh_src[t] = src;
+    sh_step[t] = EPI == 1 ? p.krow[src] : 0;
+  }
+
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -375,10 +386,11 @@ __global__ __launch_bounds__(512) void kernel_hs(Args p) {
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int gm = tile_m * BM + wm * 128 + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+      const int lm = wm * 128 + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+      const int gm = tile_m * BM + lm;
       if (gm >= M) continue;
-      const int src = p.rowidx[gm];
-      const float* brow = EPI == 1 ? p.bias + static_cast<size_t>(p.krow[src]) * p.N : p.bias;
+      const int src = sh_src[lm];
+      const float* brow = EPI == 1 ? p.bias + static_cast<size_t>(sh_step[lm]) * p.N : p.bias;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int gn = tile_n * BN + wn * 64 + j * 32 + l32;
