@@ -119,6 +119,16 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
     }
   }
 
+  // the epilogue's row bookkeeping is fetched now, one row per thread, and parked in LDS (see kernel_hs)
+  static_assert(BM <= 64 * WM * WN, "one thread per tile row");
+  __shared__ int sh_src[BM], sh_step[BM];
+  if (t < BM) {
+    const int gm = tile_m * BM + t;
+    const int src = p.rowidx[gm < M ? gm : M - 1];
+    sh_src[t] = src;
+    sh_step[t] = EPI == 1 ? p.krow[src] : 0;
+  }
+
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -188,10 +198,11 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int gm = tile_m * BM + wm * (BM / WM) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+      const int lm = wm * (BM / WM) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+      const int gm = tile_m * BM + lm;
       if (gm >= M) continue;
-      const int src = p.rowidx[gm];
-      const float* brow = EPI == 1 ? p.bias + static_cast<size_t>(p.krow[src]) * p.N : p.bias;
+      const int src = sh_src[lm];
+      const float* brow = EPI == 1 ? p.bias + static_cast<size_t>(sh_step[lm]) * p.N : p.bias;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
