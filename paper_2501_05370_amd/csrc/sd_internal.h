@@ -17,6 +17,7 @@ struct sd_ctx {
   float* dev_a = nullptr;       // [T] each, one allocation of 3T floats
   float* dev_c = nullptr;
   float* dev_sigma = nullptr;
+  int32_t* dev_queue = nullptr;  // [2] zeroed counters behind the schedule (chain dispenser of the Langevin kernel)
   const int32_t* active = nullptr;
   const float* carry_src = nullptr;    // FROZEN_REUSED: predictions [B,K+1,d] of the window just verified
   float* carry_dst = nullptr;          //   and the [B,d] frozen predictions sd_advance fills for the next one

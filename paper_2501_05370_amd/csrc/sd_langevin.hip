@@ -37,6 +37,7 @@ struct LangevinArgs {
   uint8_t* rej;
   float *logratio, *logu;
   const int32_t* active;
+  int32_t* queue;       // [2] chain dispenser of the wavefront kernel: next chain, wavefronts that have left
   int B, d, K, T, M;
   uint64_t seed;
   double gamma, inv_s2, inv_tau;
@@ -303,16 +304,24 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   __syncthreads();                                         // last workgroup-wide barrier
 
   const int Bact = p.active ? min(p.B, max(0, *p.active)) : p.B;
-  const int b = blockIdx.x * kWaveChains + wave;
-  if (b >= Bact) return;                                   // whole wavefront leaves
-  const int n = p.n[b];
-  const int Kt = max(0, min(p.K, p.T - n));
-  const int64_t id = p.id[b];
   const double gamma = p.gamma, inv_s2 = p.inv_s2;
   const double sq2g = sqrt(2.0 * gamma), sqg2 = sqrt(0.5 * gamma), inv_sqg2 = 1.0 / sqg2;
   const int my_m = lane >> 2;                              // component this lane holds after a reduction
   const double my_logw = my_m < M ? static_cast<double>(p.logw[my_m]) : 0.0;
   const double my_hn = sh_hn[my_m];
+
+  // The workgroup keeps its copy of the means for the whole launch (the table is staged once per resident
+  // workgroup, not once per four chains) and its wavefronts, independent from here on, take chains one at a
+  // time from a counter: a chain's window ends at its first rejection, so the work per chain varies by an
+  // order of magnitude and a fixed split would leave most of the chip waiting for the unluckiest wavefront.
+  for (;;) {
+  int ticket = 0;
+  if (lane == 0) ticket = atomicAdd(&p.queue[0], 1);
+  const int b = __builtin_amdgcn_readfirstlane(ticket);
+  if (b >= Bact) break;
+  const int n = p.n[b];
+  const int Kt = max(0, min(p.K, p.T - n));
+  const int64_t id = p.id[b];
 
   bool own[CPT][4];
   double cur[CPT][4];
@@ -459,6 +468,16 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
     for (int e = 0; e < 4; ++e)
       if (own[c][e]) p.x_out[static_cast<int64_t>(b) * d + i0 + e] = static_cast<float>(cur[c][e]);
   }
+  }                                                        // next chain of this wavefront
+  // The last wavefront to leave rewinds the dispenser for the next launch: every other wavefront drew its
+  // final ticket before it counted itself out.
+  if (lane == 0) {
+    const int total = static_cast<int>(gridDim.x) * kWaveChains;
+    if (atomicAdd(&p.queue[1], 1) == total - 1) {
+      atomicExch(&p.queue[0], 0);
+      atomicExch(&p.queue[1], 0);
+    }
+  }
 }
 
 template <int CPT>
@@ -471,7 +490,16 @@ hipError_t launch_wave(const LangevinArgs& p, int dpad, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const unsigned grid = static_cast<unsigned>((p.B + kWaveChains - 1) / kWaveChains);
+  static int resident = 0;                                 // workgroups the chip holds at once (2 per CU)
+  if (resident == 0) {
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    resident = 2 * (cus > 0 ? cus : 256);
+  }
+  const int groups = (p.B + kWaveChains - 1) / kWaveChains;
+  const unsigned grid = static_cast<unsigned>(groups < resident ? groups : resident);
   hipLaunchKernelGGL(langevin_window_wave_kernel<CPT>, dim3(grid), dim3(64 * kWaveChains), shmem, st, p, dpad);
   return hipGetLastError();
 }
@@ -657,7 +685,7 @@ extern "C" int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const 
                      ctx->d, 4 * 4 * kThreads);
   LangevinArgs p;
   p.x = x; p.n = n; p.id = chain_id; p.means = means; p.logw = logw; p.x_out = x_out; p.adv = adv;
-  p.rej = rejected; p.logratio = logratio; p.logu = logu; p.active = ctx->active;
+  p.rej = rejected; p.logratio = logratio; p.logu = logu; p.active = ctx->active; p.queue = ctx->dev_queue;
   p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.M = M; p.seed = ctx->seed;
   p.gamma = gamma; p.inv_s2 = 1.0 / (static_cast<double>(comp_std) * comp_std); p.inv_tau = 1.0 / ctx->tau;
   hipStream_t st = static_cast<hipStream_t>(stream);

@@ -676,7 +676,9 @@ int sd_create(const sd_schedule* s, int32_t d, int32_t K, sd_ctx** out) {
   ctx->T = s->T; ctx->d = d; ctx->K = K;
   hipError_t e = hipGetDevice(&ctx->device);
   float* dev = nullptr;
-  if (e == hipSuccess) e = hipMalloc(&dev, sizeof(float) * 3 * static_cast<size_t>(s->T));
+  const size_t sched_floats = (3 * static_cast<size_t>(s->T) + 15) / 16 * 16;   // counters start 64-byte aligned
+  if (e == hipSuccess) e = hipMalloc(&dev, sizeof(float) * sched_floats + 64);
+  if (e == hipSuccess) e = hipMemset(dev + sched_floats, 0, 64);
   if (e == hipSuccess) e = hipMemcpy(dev, s->a, sizeof(float) * s->T, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(dev + s->T, s->c, sizeof(float) * s->T, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(dev + 2 * s->T, s->sigma, sizeof(float) * s->T, hipMemcpyHostToDevice);
@@ -686,6 +688,7 @@ int sd_create(const sd_schedule* s, int32_t d, int32_t K, sd_ctx** out) {
     return sdi::fail(g_create_error, SD_ERR_HIP, "sd_create: %s", hipGetErrorString(e));
   }
   ctx->dev_a = dev; ctx->dev_c = dev + s->T; ctx->dev_sigma = dev + 2 * s->T;
+  ctx->dev_queue = reinterpret_cast<int32_t*>(dev + sched_floats);
   *out = ctx;
   return SD_OK;
 }
