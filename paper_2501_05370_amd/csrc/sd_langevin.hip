@@ -19,6 +19,7 @@
 #include <cmath>
 
 #include "sd_internal.h"
+#include "sd_lanes.h"
 #include "sd_rng.h"
 
 namespace {
@@ -43,10 +44,18 @@ struct LangevinArgs {
   double gamma, inv_s2, inv_tau;
 };
 
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-  return v;
+__device__ __forceinline__ double wave_sum(double v) { return sdlane::wave_sum(v); }
+
+// v of lane (lane ^ mask), mask a single bit known at compile time after unrolling
+__device__ __forceinline__ double dpp_xor(double v, int mask) {
+  switch (mask) {
+    case 1: return sdlane::lane_xor<1>(v);
+    case 2: return sdlane::lane_xor<2>(v);
+    case 4: return sdlane::lane_xor<4>(v);
+    case 8: return sdlane::lane_xor<8>(v);
+    case 16: return sdlane::lane_xor<16>(v);
+    default: return sdlane::lane_xor<32>(v);
+  }
 }
 
 // CPT: float4 groups per thread; MMAX: compile-time bound on the number of components.
@@ -114,7 +123,7 @@ __global__ __launch_bounds__(kThreads) void langevin_window_kernel(LangevinArgs 
       }
       double mx = logit;
 #pragma unroll
-      for (int s = 32; s >= 1; s >>= 1) mx = fmax(mx, __shfl_xor(mx, s, 64));
+      for (int s = 32; s >= 1; s >>= 1) mx = fmax(mx, dpp_xor(mx, s));
       const double ex = t < M ? exp(logit - mx) : 0.0;
       const double sum = wave_sum(ex);
       if (t < M) sh_r[t] = ex / sum;
@@ -226,7 +235,6 @@ __global__ __launch_bounds__(kThreads) void langevin_window_kernel(LangevinArgs 
 constexpr int kWaveChains = 4;             // chains (wavefronts) per workgroup
 constexpr int kWaveM = 16;                 // components handled by the transposed reduction
 
-__device__ __forceinline__ double dpp_xor(double v, int mask) { return __shfl_xor(v, mask, 64); }
 
 // in: 16 per-lane partial sums; out: total of value ((lane >> 2) & 15), on every lane
 __device__ __forceinline__ double reduce16_transposed(double (&a)[16], int lane) {
@@ -531,7 +539,7 @@ struct Phi4Args {
 template <int G>
 __device__ __forceinline__ double group_sum_f64(double v) {
 #pragma unroll
-  for (int s = G / 2; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+  for (int s = G / 2; s >= 1; s >>= 1) v += dpp_xor(v, s);
   return v;
 }
 
