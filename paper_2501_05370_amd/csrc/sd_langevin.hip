@@ -289,6 +289,11 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   __shared__ double sh_hn[kWaveM];                         // |mu_m|^2 / 2
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int d = p.d, M = p.M;
+  // Rows are read as whole float4s through this view, indexed in units of 16 bytes: with the row stride a
+  // run-time number of floats the compiler cannot see that a row starts 16-byte aligned and splits every
+  // 128-bit LDS read into 32-bit pairs, which are slower and collide on the banks.
+  const float4* sh_mu4 = reinterpret_cast<const float4*>(sh_mu);
+  const int dpad4 = dpad >> 2;                             // dpad is a multiple of 4
 
   for (int idx = t; idx < kWaveM * dpad; idx += 64 * kWaveChains) {
     const int m = idx / dpad, i = idx % dpad;
@@ -354,7 +359,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
       if (4 * g4 < dpad) {
 #pragma unroll
         for (int m = 0; m < kWaveM; ++m) {
-          const float4 mu = *reinterpret_cast<const float4*>(&sh_mu[m * dpad + 4 * g4]);
+          const float4 mu = sh_mu4[m * dpad4 + g4];
           dot[m] = fma(cur[c][0], static_cast<double>(mu.x), dot[m]);
           dot[m] = fma(cur[c][1], static_cast<double>(mu.y), dot[m]);
           dot[m] = fma(cur[c][2], static_cast<double>(mu.z), dot[m]);
@@ -388,7 +393,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
       for (int c = 0; c < CPT; ++c) {
         const int g4 = lane + 64 * c;
         if (4 * g4 < dpad) {
-          const float4 mu = *reinterpret_cast<const float4*>(&sh_mu[m * dpad + 4 * g4]);
+          const float4 mu = sh_mu4[m * dpad4 + g4];
           bar[c][0] = fma(r, static_cast<double>(mu.x), bar[c][0]);
           bar[c][1] = fma(r, static_cast<double>(mu.y), bar[c][1]);
           bar[c][2] = fma(r, static_cast<double>(mu.z), bar[c][2]);
