@@ -68,6 +68,43 @@ __device__ __forceinline__ double pair_sum_rows(double v) {
   return a + b;
 }
 
+// Halving step of a transposed reduction at distance MASK: a lane whose bit MASK is clear keeps `lower`, a
+// lane whose bit is set keeps `upper`, and each adds its partner's copy of the value it keeps.  For the two
+// row-swap masks one swap per 32-bit half delivers exactly that with no select; for 4 the two shifted moves
+// are written under bank masks so the operand needs no select either.
+template <int MASK>
+__device__ __forceinline__ double halving_add(double lower, double upper) {
+  const long long lb = __double_as_longlong(lower), ub = __double_as_longlong(upper);
+  const unsigned l0 = static_cast<unsigned>(lb), l1 = static_cast<unsigned>(lb >> 32);
+  const unsigned u0 = static_cast<unsigned>(ub), u1 = static_cast<unsigned>(ub >> 32);
+  if constexpr (MASK == 16 || MASK == 32) {
+    uint2v r0, r1;
+    if constexpr (MASK == 16) {
+      r0 = __builtin_amdgcn_permlane16_swap(l0, u0, false, false);
+      r1 = __builtin_amdgcn_permlane16_swap(l1, u1, false, false);
+    } else {
+      r0 = __builtin_amdgcn_permlane32_swap(l0, u0, false, false);
+      r1 = __builtin_amdgcn_permlane32_swap(l1, u1, false, false);
+    }
+    const double a = __longlong_as_double((static_cast<long long>(r1[0]) << 32) | r0[0]);
+    const double b = __longlong_as_double((static_cast<long long>(r1[1]) << 32) | r0[1]);
+    return a + b;
+  } else {
+    const bool up = __lane_id() & MASK;
+    const double keep = up ? upper : lower;
+    if constexpr (MASK == 4) {
+      int g0 = __builtin_amdgcn_update_dpp(0, static_cast<int>(l0), 0x104, 0xF, 0x5, false);
+      g0 = __builtin_amdgcn_update_dpp(g0, static_cast<int>(u0), 0x114, 0xF, 0xA, false);
+      int g1 = __builtin_amdgcn_update_dpp(0, static_cast<int>(l1), 0x104, 0xF, 0x5, false);
+      g1 = __builtin_amdgcn_update_dpp(g1, static_cast<int>(u1), 0x114, 0xF, 0xA, false);
+      return keep + __longlong_as_double((static_cast<long long>(g1) << 32) | static_cast<unsigned>(g0));
+    } else {
+      const double send = up ? lower : upper;
+      return keep + lane_xor<MASK>(send);
+    }
+  }
+}
+
 // Sum over the wavefront, the same bits on every lane.
 __device__ __forceinline__ double wave_sum(double v) {
   v += lane_xor<1>(v);

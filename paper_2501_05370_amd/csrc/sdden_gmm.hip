@@ -15,6 +15,7 @@
 #include <new>
 #include <vector>
 
+#include "sd_lanes.h"
 #include "sdden_internal.h"
 
 namespace sdi {
@@ -25,12 +26,15 @@ namespace {
 
 constexpr int kRowsPerBlock = 4;
 
+constexpr int kRegNI = 32;   // coordinates per lane of the register-resident kernel
+
 struct GmmArgs {
   const float* X;
   const int32_t* krow;
   float* out;
   const float *mu, *sd;      // [M,d]  component means and stds
   const float *muT, *sdT;    // [d,M]  the same, transposed
+  const float2* lane_tab;    // [kRegNI,64] (mean, std) in the lane order of the register kernel, or null
   const double* cst;         // [T,M]  log w_m - 1/2 sum_i log v_mi(k)
   int Mp;                    // M rounded up to a power of two (<= 64), lanes per coordinate slice
   const float* ab;           // [T+1]
@@ -135,11 +139,35 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_kernel(
 // per-component posterior mean of its (component, coordinate) pairs in the same pass as the quadratic
 // form and keeps it in registers, so the reciprocal variance and x - sqrt(ab) mu are computed once
 // instead of once per phase.
-// Lane = (component m, part); the lane owns coordinates i = part + PARTS * j, j < NI.  Phase 1 sums
-// its quadratic form and finishes it across the parts; the softmax runs across the MP lanes of a
-// part; phase 2 scales the kept means by r_m and a
-// halving exchange over the component lanes leaves each lane with the finished sums of NI / MP
-// coordinates, which it writes.  No LDS, no barrier.
+// Lane = part + PARTS * m (component m, PARTS = 64 / MP lanes per component); the lane owns coordinates
+// i = part + PARTS * j, j < NI.  Phase 1 sums its quadratic form and finishes it across the parts; the
+// softmax runs across the component lanes; phase 2 scales the kept means by r_m and a halving exchange over
+// the component lanes leaves each lane with the finished sums of NI / MP coordinates, which it writes.
+// The component index sits in the high lane bits so that the two largest levels of the exchange (half
+// and a quarter of the list) are row swaps, one instruction per 32-bit word with no select.
+// No LDS, no barrier.
+__device__ __forceinline__ double lane_xor_f64(double v, int mask) {   // mask: one bit, constant after unrolling
+  switch (mask) {
+    case 1: return sdlane::lane_xor<1>(v);
+    case 2: return sdlane::lane_xor<2>(v);
+    case 4: return sdlane::lane_xor<4>(v);
+    case 8: return sdlane::lane_xor<8>(v);
+    case 16: return sdlane::lane_xor<16>(v);
+    default: return sdlane::lane_xor<32>(v);
+  }
+}
+
+__device__ __forceinline__ double halving_add_f64(double lower, double upper, int mask) {
+  switch (mask) {
+    case 1: return sdlane::halving_add<1>(lower, upper);
+    case 2: return sdlane::halving_add<2>(lower, upper);
+    case 4: return sdlane::halving_add<4>(lower, upper);
+    case 8: return sdlane::halving_add<8>(lower, upper);
+    case 16: return sdlane::halving_add<16>(lower, upper);
+    default: return sdlane::halving_add<32>(lower, upper);
+  }
+}
+
 template <int MP, int NI>
 __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_reg_kernel(GmmArgs p) {
   static_assert(NI % MP == 0 && MP <= 32 && (MP & (MP - 1)) == 0, "component lanes must divide the coordinate list");
@@ -151,7 +179,7 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_reg_ker
   if (k < 0) return;                        // whole wavefront leaves together
   const double ab = p.ab[k];
   const double sab = sqrt(ab), om = 1.0 - ab;
-  const int m = lane % MP, part = lane / MP;
+  const int part = lane % PARTS, m = lane / PARTS;
   const bool live = m < p.M;
   const float* x = p.X + static_cast<int64_t>(r) * p.d;
 
@@ -162,8 +190,8 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_reg_ker
     const int i = part + PARTS * j;
     v[j] = 0.0;
     if (live && i < p.d) {
-      const double mu = p.muT[static_cast<int64_t>(i) * p.M + m];
-      const double sd = p.sdT[static_cast<int64_t>(i) * p.M + m];
+      const float2 ms = p.lane_tab[j * 64 + lane];           // one coalesced 512-byte read per wavefront
+      const double mu = ms.x, sd = ms.y;
       const double s2 = sd * sd;
       const double iv = reciprocal_one_step(fma(ab, s2, om));
       const double df = fma(-sab, mu, static_cast<double>(x[i]));
@@ -172,33 +200,27 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_reg_ker
     }
   }
 #pragma unroll
-  for (int s = MP; s < 64; s <<= 1) q += __shfl_xor(q, s, 64);
+  for (int s = 1; s < PARTS; s <<= 1) q += lane_xor_f64(q, s);
   const double logit = live ? p.cst[static_cast<int64_t>(k) * p.M + m] - 0.5 * q : -INFINITY;
   double mx = logit;
 #pragma unroll
-  for (int s = MP / 2; s >= 1; s >>= 1) mx = fmax(mx, __shfl_xor(mx, s, 64));
+  for (int s = PARTS; s < 64; s <<= 1) mx = fmax(mx, lane_xor_f64(mx, s));
   const double e = live ? exp(logit - mx) : 0.0;
   double sum = e;
 #pragma unroll
-  for (int s = MP / 2; s >= 1; s >>= 1) sum += __shfl_xor(sum, s, 64);
+  for (int s = PARTS; s < 64; s <<= 1) sum += lane_xor_f64(sum, s);
   const double rm = e / sum;
 #pragma unroll
   for (int j = 0; j < NI; ++j) v[j] *= rm;
-  // halving exchange over the component lanes: at distance s a lane keeps the upper half of its list if its
-  // bit s is set (else the lower half) and receives the partner's sums for that half
+  // halving exchange over the component lanes: at component distance s a lane keeps the upper half of its
+  // list if bit s of its component is set (else the lower half) and adds the partner's sums for that half
   int n = NI;
 #pragma unroll
   for (int s = MP / 2; s >= 1; s >>= 1) {
-    const bool up = lane & s;
     n >>= 1;
 #pragma unroll
-    for (int j = 0; j < NI / 2; ++j) {
-      if (j < n) {
-        const double send = up ? v[j] : v[j + n];
-        const double keep = up ? v[j + n] : v[j];
-        v[j] = keep + __shfl_xor(send, s, 64);
-      }
-    }
+    for (int j = 0; j < NI / 2; ++j)
+      if (j < n) v[j] = halving_add_f64(v[j], v[j + n], s * PARTS);
   }
   constexpr int C = NI / MP;                // finished coordinates per lane: j = m * C + jj
   float* o = p.out + static_cast<int64_t>(r) * p.d;
@@ -215,8 +237,9 @@ void launch_reg(const GmmArgs& p, unsigned grid, hipStream_t st) {
 }
 
 struct GmmDenoiser final : sdden {
-  int M = 0;
-  float* dev_f = nullptr;     // mu, sd, muT, sdT, ab
+  int M = 0, Mp = 1;          // Mp: M rounded up to a power of two, at most 64
+  float* dev_f = nullptr;     // mu, sd, muT, sdT, ab, then the lane-ordered table when the register kernel applies
+  const float2* lane_tab = nullptr;
   double* dev_cst = nullptr;
   ~GmmDenoiser() override {
     if (dev_f) (void)hipFree(dev_f);
@@ -227,15 +250,14 @@ struct GmmDenoiser final : sdden {
     const size_t md = static_cast<size_t>(M) * d;
     p.X = X; p.krow = krow; p.out = out;
     p.mu = dev_f; p.sd = dev_f + md; p.muT = dev_f + 2 * md; p.sdT = dev_f + 3 * md; p.ab = dev_f + 4 * md;
-    p.Mp = 1;
-    while (p.Mp < M && p.Mp < 64) p.Mp <<= 1;
+    p.Mp = Mp;
+    p.lane_tab = lane_tab;
     p.cst = dev_cst; p.active = active; p.rows_per_chain = rows_per_chain;
     p.R = R; p.d = d; p.M = M;
     const size_t shmem = sizeof(double) * kRowsPerBlock * static_cast<size_t>(M + d);
     const unsigned grid = static_cast<unsigned>((R + kRowsPerBlock - 1) / kRowsPerBlock);
-    constexpr int kRegNI = 32;               // coordinates per lane of the register-resident kernel
     prof.mark(1, st);
-    if (p.Mp <= 32 && d <= (64 / p.Mp) * kRegNI) {
+    if (lane_tab) {
       switch (p.Mp) {
         case 32: launch_reg<32, kRegNI>(p, grid, st); break;
         case 16: launch_reg<16, kRegNI>(p, grid, st); break;
@@ -277,6 +299,23 @@ int sdden_gmm_create(int32_t M, int32_t d, const float* means, const float* stds
       h[3 * md + i * static_cast<size_t>(M) + m] = s;
     }
   for (int k = 0; k <= T; ++k) h[4 * md + k] = alpha_bar_state[k];
+  int Mp = 1;
+  while (Mp < M && Mp < 64) Mp <<= 1;
+  size_t lane_off = 0;
+  if (Mp <= 32 && d <= (64 / Mp) * kRegNI) {
+    // (mean, std) of the pair that lane part + PARTS * m reads at its j-th coordinate i = part + PARTS * j;
+    // slots without a pair hold (0, 1) and are never used
+    const int parts = 64 / Mp;
+    lane_off = (h.size() + 1) / 2 * 2;                       // 8-byte aligned
+    h.resize(lane_off + 2 * static_cast<size_t>(kRegNI) * 64);
+    for (int j = 0; j < kRegNI; ++j)
+      for (int lane = 0; lane < 64; ++lane) {
+        const int part = lane % parts, m = lane / parts, i = part + parts * j;
+        const bool has = m < M && i < d;
+        h[lane_off + 2 * (static_cast<size_t>(j) * 64 + lane)] = has ? means[m * static_cast<size_t>(d) + i] : 0.f;
+        h[lane_off + 2 * (static_cast<size_t>(j) * 64 + lane) + 1] = has ? stds[m * static_cast<size_t>(d) + i] : 1.f;
+      }
+  }
   for (int k = 0; k < T; ++k) {
     const double ab = alpha_bar_state[k];
     for (int m = 0; m < M; ++m) {
@@ -299,6 +338,8 @@ int sdden_gmm_create(int32_t M, int32_t d, const float* means, const float* stds
     delete g;
     return sdi::fail(E, SD_ERR_HIP, "sdden_gmm_create: %s", hipGetErrorString(e));
   }
+  g->Mp = Mp;
+  if (lane_off) g->lane_tab = reinterpret_cast<const float2*>(g->dev_f + lane_off);
   *out = g;
   return SD_OK;
 }
