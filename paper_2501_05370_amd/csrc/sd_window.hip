@@ -9,6 +9,7 @@
 #include <new>
 
 #include "sd_internal.h"
+#include "sd_lanes.h"
 #include "sd_rng.h"
 
 namespace {
@@ -50,8 +51,12 @@ __device__ __forceinline__ int active_chains(const int32_t* active, int B) {
 // Sum over the `WIDTH` consecutive lanes this lane belongs to; every lane gets the total.
 template <int WIDTH>
 __device__ __forceinline__ double group_sum(double v) {
-#pragma unroll
-  for (int m = WIDTH / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, WIDTH);
+  if constexpr (WIDTH >= 2) v += sdlane::lane_xor<1>(v);
+  if constexpr (WIDTH >= 4) v += sdlane::lane_xor<2>(v);
+  if constexpr (WIDTH >= 8) v += sdlane::lane_xor<4>(v);
+  if constexpr (WIDTH >= 16) v += sdlane::lane_xor<8>(v);
+  if constexpr (WIDTH >= 32) v = sdlane::pair_sum_rows<16>(v);
+  if constexpr (WIDTH >= 64) v = sdlane::pair_sum_rows<32>(v);
   return v;
 }
 
