@@ -232,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void langevin_window_kernel(LangevinArgs 
 // butterfly (values are exchanged in halves, 17 shuffles instead of 96); responsibilities are then
 // broadcast through scalar registers.
 // ---------------------------------------------------------------------------------------------
-constexpr int kWaveChains = 4;             // chains (wavefronts) per workgroup
+constexpr int kWaveChains = 8;             // chains (wavefronts) per workgroup: one workgroup fills a CU at 2 per SIMD
 constexpr int kWaveM = 16;                 // components handled by the transposed reduction
 
 
@@ -285,19 +285,28 @@ __device__ __forceinline__ double readlane_f64(double v, int src_lane) {
 
 template <int CPT>
 __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kernel(LangevinArgs p, int dpad) {
-  extern __shared__ __align__(16) float sh_mu[];          // [kWaveM][dpad], rows beyond M and the pad are 0
+  // [kWaveM][dpad] as fp64 (rows beyond M and the pad are 0): converted once here instead of once per use --
+  // the logit pass is one FMA per table element, and a conversion beside each would be a fifth of all
+  // vector instructions of the kernel.  16 x 1024 doubles = 128 KiB: one workgroup of 8 wavefronts per CU.
+  extern __shared__ __align__(16) double sh_mu[];
   __shared__ double sh_hn[kWaveM];                         // |mu_m|^2 / 2
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int d = p.d, M = p.M;
   // Rows are read as whole float4s through this view, indexed in units of 16 bytes: with the row stride a
   // run-time number of floats the compiler cannot see that a row starts 16-byte aligned and splits every
   // 128-bit LDS read into 32-bit pairs, which are slower and collide on the banks.
-  const float4* sh_mu4 = reinterpret_cast<const float4*>(sh_mu);
-  const int dpad4 = dpad >> 2;                             // dpad is a multiple of 4
+  // Row layout: a row has kRow = 256 * CPT doubles; the four coordinates 4 g .. 4 g + 3 of group g = lane + 64 c
+  // sit as two halves, (e = 0, 1) at c * 256 + 2 * lane and (e = 2, 3) at c * 256 + 128 + 2 * lane, so that each
+  // of the two 128-bit reads of a group is contiguous over the lanes (conflict-free, and the row stride is a
+  // compile-time multiple of 16 bytes).
+  constexpr int kRow = 256 * CPT;
+  const double2* sh_mu2 = reinterpret_cast<const double2*>(sh_mu);
 
-  for (int idx = t; idx < kWaveM * dpad; idx += 64 * kWaveChains) {
-    const int m = idx / dpad, i = idx % dpad;
-    sh_mu[idx] = (m < M && i < d) ? p.means[static_cast<int64_t>(m) * d + i] : 0.f;
+  for (int idx = t; idx < kWaveM * kRow; idx += 64 * kWaveChains) {
+    const int m = idx / kRow, i = idx % kRow;            // i: coordinate
+    const int c = i >> 8, ln = (i & 255) >> 2, e = i & 3;
+    const int pos = c * 256 + (e < 2 ? 2 * ln + e : 128 + 2 * ln + (e - 2));
+    sh_mu[m * kRow + pos] = (m < M && i < d) ? static_cast<double>(p.means[static_cast<int64_t>(m) * d + i]) : 0.0;
   }
   __syncthreads();
   if (wave == 0) {                                         // half squared norms, fp64
@@ -305,8 +314,8 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
 #pragma unroll
     for (int m = 0; m < kWaveM; ++m) {
       double acc = 0.0;
-      for (int i = lane; i < dpad; i += 64) {
-        const double v = sh_mu[m * dpad + i];
+      for (int i = lane; i < kRow; i += 64) {
+        const double v = sh_mu[m * kRow + i];
         acc = fma(v, v, acc);
       }
       part[m] = acc;
@@ -359,11 +368,11 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
       if (4 * g4 < dpad) {
 #pragma unroll
         for (int m = 0; m < kWaveM; ++m) {
-          const float4 mu = sh_mu4[m * dpad4 + g4];
-          dot[m] = fma(cur[c][0], static_cast<double>(mu.x), dot[m]);
-          dot[m] = fma(cur[c][1], static_cast<double>(mu.y), dot[m]);
-          dot[m] = fma(cur[c][2], static_cast<double>(mu.z), dot[m]);
-          dot[m] = fma(cur[c][3], static_cast<double>(mu.w), dot[m]);
+          const double2 lo = sh_mu2[m * (kRow / 2) + c * 128 + lane], hi = sh_mu2[m * (kRow / 2) + c * 128 + 64 + lane];
+          dot[m] = fma(cur[c][0], lo.x, dot[m]);
+          dot[m] = fma(cur[c][1], lo.y, dot[m]);
+          dot[m] = fma(cur[c][2], hi.x, dot[m]);
+          dot[m] = fma(cur[c][3], hi.y, dot[m]);
         }
       }
     }
@@ -393,11 +402,11 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
       for (int c = 0; c < CPT; ++c) {
         const int g4 = lane + 64 * c;
         if (4 * g4 < dpad) {
-          const float4 mu = sh_mu4[m * dpad4 + g4];
-          bar[c][0] = fma(r, static_cast<double>(mu.x), bar[c][0]);
-          bar[c][1] = fma(r, static_cast<double>(mu.y), bar[c][1]);
-          bar[c][2] = fma(r, static_cast<double>(mu.z), bar[c][2]);
-          bar[c][3] = fma(r, static_cast<double>(mu.w), bar[c][3]);
+          const double2 lo = sh_mu2[m * (kRow / 2) + c * 128 + lane], hi = sh_mu2[m * (kRow / 2) + c * 128 + 64 + lane];
+          bar[c][0] = fma(r, lo.x, bar[c][0]);
+          bar[c][1] = fma(r, lo.y, bar[c][1]);
+          bar[c][2] = fma(r, hi.x, bar[c][2]);
+          bar[c][3] = fma(r, hi.y, bar[c][3]);
         }
       }
     }
@@ -495,21 +504,21 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
 
 template <int CPT>
 hipError_t launch_wave(const LangevinArgs& p, int dpad, hipStream_t st) {
-  const size_t shmem = sizeof(float) * kWaveM * static_cast<size_t>(dpad);
+  const size_t shmem = sizeof(double) * kWaveM * static_cast<size_t>(256 * CPT);
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&langevin_window_wave_kernel<CPT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  static int resident = 0;                                 // workgroups the chip holds at once (2 per CU)
+  static int resident = 0;                                 // workgroups the chip holds at once (1 per CU)
   if (resident == 0) {
     int dev = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
-    resident = 2 * (cus > 0 ? cus : 256);
+    resident = cus > 0 ? cus : 256;
   }
   const int groups = (p.B + kWaveChains - 1) / kWaveChains;
   const unsigned grid = static_cast<unsigned>(groups < resident ? groups : resident);
