@@ -238,41 +238,16 @@ constexpr int kWaveM = 16;                 // components handled by the transpos
 
 // in: 16 per-lane partial sums; out: total of value ((lane >> 2) & 15), on every lane
 __device__ __forceinline__ double reduce16_transposed(double (&a)[16], int lane) {
-  {
-    const bool up = lane & 32;
+  (void)lane;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const double send = up ? a[i] : a[i + 8];
-      const double keep = up ? a[i + 8] : a[i];
-      a[i] = keep + dpp_xor(send, 32);
-    }
-  }
-  {
-    const bool up = lane & 16;
+  for (int i = 0; i < 8; ++i) a[i] = sdlane::halving_add<32>(a[i], a[i + 8]);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const double send = up ? a[i] : a[i + 4];
-      const double keep = up ? a[i + 4] : a[i];
-      a[i] = keep + dpp_xor(send, 16);
-    }
-  }
-  {
-    const bool up = lane & 8;
+  for (int i = 0; i < 4; ++i) a[i] = sdlane::halving_add<16>(a[i], a[i + 4]);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const double send = up ? a[i] : a[i + 2];
-      const double keep = up ? a[i + 2] : a[i];
-      a[i] = keep + dpp_xor(send, 8);
-    }
-  }
-  {
-    const bool up = lane & 4;
-    const double send = up ? a[0] : a[1];
-    const double keep = up ? a[1] : a[0];
-    a[0] = keep + dpp_xor(send, 4);
-  }
-  a[0] += dpp_xor(a[0], 2);
-  a[0] += dpp_xor(a[0], 1);
+  for (int i = 0; i < 2; ++i) a[i] = sdlane::halving_add<8>(a[i], a[i + 2]);
+  a[0] = sdlane::halving_add<4>(a[0], a[1]);
+  a[0] += sdlane::lane_xor<2>(a[0]);
+  a[0] += sdlane::lane_xor<1>(a[0]);
   return a[0];
 }
 
@@ -433,9 +408,14 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
     bool reject = false;
     if (j > 0) gradient(dl);                               // position 1: the target gradient IS g0
     // the noise and the uniform are drawn after the gradient, which is the register-hungry part
+    // Coordinates past d (the tail of the last group) get no noise: their state starts at 0 and the means table
+    // is 0 there, so state, gradients and Delta stay exactly 0 and need no masking anywhere else.
 #pragma unroll
-    for (int c = 0; c < CPT; ++c)
+    for (int c = 0; c < CPT; ++c) {
       sdrng::normal4(p.seed, id, k1, sdrng::kStreamNoise, static_cast<uint32_t>(lane + 64 * c), z[c]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) z[c][e] = own[c][e] ? z[c][e] : 0.f;
+    }
     const double lu = readlane_f64(lu_mine, j);
     if (j > 0) {
       double a1 = 0.0, a2 = 0.0;
@@ -443,7 +423,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
       for (int c = 0; c < CPT; ++c)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          dl[c][e] = own[c][e] ? sqg2 * (dl[c][e] - g0[c][e]) : 0.0;
+          dl[c][e] = sqg2 * (dl[c][e] - g0[c][e]);
           a1 = fma(static_cast<double>(z[c][e]), dl[c][e], a1);
           a2 = fma(dl[c][e], dl[c][e], a2);
         }
@@ -462,16 +442,15 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
       for (int c = 0; c < CPT; ++c)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (own[c][e])                                   // target gradient = g0 + Delta / sqrt(gamma/2)
-            cur[c][e] = cur[c][e] - gamma * (g0[c][e] + dl[c][e] * inv_sqg2) +
-                        sq2g * (static_cast<double>(z[c][e]) - 2.0 * coef * dl[c][e]);
+          cur[c][e] = cur[c][e] - gamma * (g0[c][e] + dl[c][e] * inv_sqg2) +   // target gradient = g0 + Delta / sqrt(gamma/2)
+                      sq2g * (static_cast<double>(z[c][e]) - 2.0 * coef * dl[c][e]);
       break;
     }
 #pragma unroll
     for (int c = 0; c < CPT; ++c)
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        if (own[c][e]) cur[c][e] = cur[c][e] - gamma * g0[c][e] + sq2g * static_cast<double>(z[c][e]);
+        cur[c][e] = cur[c][e] - gamma * g0[c][e] + sq2g * static_cast<double>(z[c][e]);
   }
 
   if (lane == 0) {
