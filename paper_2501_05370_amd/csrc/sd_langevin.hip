@@ -258,7 +258,9 @@ __device__ __forceinline__ double readlane_f64(double v, int src_lane) {
   return __longlong_as_double((static_cast<long long>(hi) << 32) | static_cast<unsigned int>(lo));
 }
 
-template <int CPT>
+// WHOLE: d is a multiple of 4, so a group of four coordinates is inside d or outside it as a whole (one mask
+// per group instead of four).
+template <int CPT, bool WHOLE>
 __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kernel(LangevinArgs p, int dpad) {
   // [kWaveM][dpad] as fp64 (rows beyond M and the pad are 0): converted once here instead of once per use --
   // the logit pass is one FMA per table element, and a conversion beside each would be a fifth of all
@@ -327,7 +329,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
     const int i0 = 4 * (lane + 64 * c);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      own[c][e] = i0 + e < d;
+      own[c][e] = WHOLE ? i0 < d : i0 + e < d;
       cur[c][e] = own[c][e] ? static_cast<double>(p.x[static_cast<int64_t>(b) * d + i0 + e]) : 0.0;
     }
   }
@@ -481,12 +483,12 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   }
 }
 
-template <int CPT>
+template <int CPT, bool WHOLE>
 hipError_t launch_wave(const LangevinArgs& p, int dpad, hipStream_t st) {
   const size_t shmem = sizeof(double) * kWaveM * static_cast<size_t>(256 * CPT);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&langevin_window_wave_kernel<CPT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&langevin_window_wave_kernel<CPT, WHOLE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -501,7 +503,7 @@ hipError_t launch_wave(const LangevinArgs& p, int dpad, hipStream_t st) {
   }
   const int groups = (p.B + kWaveChains - 1) / kWaveChains;
   const unsigned grid = static_cast<unsigned>(groups < resident ? groups : resident);
-  hipLaunchKernelGGL(langevin_window_wave_kernel<CPT>, dim3(grid), dim3(64 * kWaveChains), shmem, st, p, dpad);
+  hipLaunchKernelGGL((langevin_window_wave_kernel<CPT, WHOLE>), dim3(grid), dim3(64 * kWaveChains), shmem, st, p, dpad);
   return hipGetLastError();
 }
 
@@ -691,13 +693,14 @@ extern "C" int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const 
   p.gamma = gamma; p.inv_s2 = 1.0 / (static_cast<double>(comp_std) * comp_std); p.inv_tau = 1.0 / ctx->tau;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int dpad = 4 * groups;
-  if (dpad <= 1024) {                       // a wavefront per chain, means in LDS (16 * dpad floats <= 64 KiB)
+  if (dpad <= 1024) {                       // a wavefront per chain, means in LDS (16 rows of doubles, <= 128 KiB)
     hipError_t e;
+    const bool whole = ctx->d % 4 == 0;
     switch ((groups + 63) / 64) {
-      case 1: e = launch_wave<1>(p, dpad, st); break;
-      case 2: e = launch_wave<2>(p, dpad, st); break;
-      case 3: e = launch_wave<3>(p, dpad, st); break;
-      default: e = launch_wave<4>(p, dpad, st); break;
+      case 1: e = whole ? launch_wave<1, true>(p, dpad, st) : launch_wave<1, false>(p, dpad, st); break;
+      case 2: e = whole ? launch_wave<2, true>(p, dpad, st) : launch_wave<2, false>(p, dpad, st); break;
+      case 3: e = whole ? launch_wave<3, true>(p, dpad, st) : launch_wave<3, false>(p, dpad, st); break;
+      default: e = whole ? launch_wave<4, true>(p, dpad, st) : launch_wave<4, false>(p, dpad, st); break;
     }
     if (e != hipSuccess) return sdi::fail(ctx->err, SD_ERR_HIP, "sd_langevin_window: %s", hipGetErrorString(e));
     return SD_OK;
