@@ -185,7 +185,11 @@ int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv,
  *   Delta_j = sqrt(gamma/2) (grad E(y~_{j-1}) - grad E(x_n)).
  * The context supplies T, K, d and the seed; its schedule arrays are not read.
  * in : x [B,d], n [B], chain_id [B]; means [M,d]; logw [M] (log weights); comp_std = s; gamma (dev)
- * out: x_out [B,d], adv [B], rejected [B] or NULL; logratio, logu [B,K] or NULL as in sd_verify. */
+ * out: x_out [B,d], adv [B], rejected [B] or NULL; logratio, logu [B,K] or NULL as in sd_verify.
+ * Calls on one context must be ordered (one stream, or events between streams): for d <= 1024 the
+ * kernel hands chains to its wavefronts through two counters that belong to the context, which the
+ * last wavefront of a launch rewinds; two launches of one context in flight at once would share
+ * them.  Different contexts are independent. */
 int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
                        const int64_t* chain_id, const float* means, const float* logw,
                        float comp_std, int32_t M, float gamma, float* x_out, int32_t* adv,
