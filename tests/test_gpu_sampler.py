@@ -81,7 +81,10 @@ def test_batch_composition_does_not_change_results():
 
 
 @pytest.mark.parametrize("B,d,M,K,T", [(64, 1000, 16, 16, 40), (40, 10, 3, 5, 12), (32, 1003, 16, 16, 30),
-                                       (16, 2100, 7, 8, 20), (8, 4096, 16, 4, 9)])
+                                       (16, 2100, 7, 8, 20), (8, 4096, 16, 4, 9),
+                                       # two and three coordinate groups per lane; more chains than the resident
+                                       # wavefronts (each wavefront then takes several chains from the counter)
+                                       (48, 512, 5, 6, 15), (24, 700, 16, 8, 20), (3000, 40, 4, 6, 14)])
 def test_langevin_window_matches_oracle(B, d, M, K, T):
     rng = np.random.default_rng(8)
     cfg = W.make_config("c5", B=B, d=d, M=M, K=K, T=T)
@@ -94,7 +97,7 @@ def test_langevin_window_matches_oracle(B, d, M, K, T):
     x = as_f32_f64(p.means[comp] * rng.uniform(0.3, 1.0, size=(B, 1)) + rng.standard_normal((B, d)))
     n = rng.integers(0, T, size=B)
     n[:3] = [T - 1, T - 2, 0]
-    ids = rng.permutation(1000)[:B].astype(np.int64)
+    ids = rng.permutation(max(1000, 2 * B))[:B].astype(np.int64)
     xo, adv, rej, lr, lu = L.ula_window(sc, x, n, ids, K, T, gamma, seed=21)
     gx = torch.full((B, d), 9.0, dtype=torch.float32, device="cuda")
     gadv = torch.zeros(B, dtype=torch.int32, device="cuda")
