@@ -50,7 +50,7 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "mfma_fp32": 
         "alu_fp64": (78.6, "TFLOP/s"), "alu_fp32": (157.3, "TFLOP/s"),
         # vector instruction issue: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (the fp32
         # figure is this times 2 for the FMA and 2 for the packed form)
-        "alu_lane": (39.3, "T lane-op/s")}
+        "alu_lane": (39.3, "T four-cycle lane-op/s")}
 
 
 def roofline_plan(cfg):
@@ -83,16 +83,21 @@ def roofline_plan(cfg):
     if cfg.kind == "langevin":
         M = cfg.params.means.shape[0]
         # fp64 flops per evaluated position: logits 3 M d, gradient 2 M d + 2 d, Delta / dots / update 12 d
-        return dict(kernel="langevin_window_wave_kernel<4> (fused draft + score + verify, one wavefront per chain)", stage="langevin_window",
+        return dict(kernel="langevin_window_wave_kernel<4> (fused draft + score + verify, one wavefront per chain; with --loop fused "
+                           "its run form: every chain's windows back to back in one launch)", stage="langevin_window",
                     bound="alu", peak="alu_fp64", scale=1e-12,
                     work=lambda c: float(c[0] + c[1]) * d * (5.0 * M + 14.0))
     if cfg.kind == "phi4":
-        # lane instructions per site and evaluated position: Philox + Box-Muller about 40 (int32 / fp32), the
-        # stencil gradient, Delta, the two dot products and the update about 30 in fp64 (two issue slots each),
-        # against the vector issue rate
-        return dict(kernel="phi4_window_kernel<16> (fused draft + stencil gradient + verify, 16 lanes per chain)",
+        # Vector work per site and evaluated position, in units of one four-cycle wavefront instruction per lane
+        # (the rate of fp64 arithmetic, conversions and 32-bit multiplies: 16 lanes per clock and SIMD; plain 32-bit
+        # operations cost half a unit, v_mad_u64_u32 1.75, transcendentals 2).  Per lane and position (4 sites):
+        # Philox4x32-10 55 (20 wide multiplies, 40 xor / add), Box-Muller for 4 normals 25, their conversion to
+        # fp64 4, stencil gradient 36, Delta and the two dot products 18, their reduction over the chain's lanes 25,
+        # update 9, accept test 8: 180 per lane, 45 per site.
+        return dict(kernel="phi4_window_kernel<16> (fused draft + stencil gradient + verify, 16 lanes per chain; with --loop fused "
+                           "phi4_run_kernel<16>: every chain's windows back to back in one launch)",
                     stage="langevin_window", bound="alu", peak="alu_lane", scale=1e-12,
-                    work=lambda c: float(c[0] + c[1]) * d * 100.0)
+                    work=lambda c: float(c[0] + c[1]) * d * 45.0)
     raise ValueError(cfg.kind)
 
 
@@ -115,14 +120,17 @@ def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1):
     smp = _sampler(cfg, drafter)
     ids = torch.arange(cfg.B, dtype=torch.int64, device="cuda")
     plan = roofline_plan(cfg)
-    run_kw = {} if loop == "eager" else dict(windows_per_sync=wps, graph=(loop == "graph"))
+    run_kw = {} if loop in ("eager", "fused") else dict(windows_per_sync=wps, graph=(loop == "graph"))
+    run = smp.run_fused if loop == "fused" else smp.run
+    if loop == "fused":
+        plan = dict(plan, stage="langevin_run")
     for w in range(warmup):
         smp.ctx.sd_set_seed(cfg.seed + 1000 + w)
-        smp.run(ids, **run_kw)
+        run(ids, **run_kw)
     torch.cuda.synchronize()
 
     den = getattr(smp, "den", None)
-    events_in_loop = loop == "eager"            # per-stage events cannot be recorded into replayed graphs
+    events_in_loop = loop in ("eager", "fused")   # per-stage events cannot be recorded into replayed graphs
     if events_in_loop:
         if stages:
             smp.timer = StageTimer()
@@ -136,7 +144,7 @@ def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1):
     t0 = time.perf_counter()
     for s in range(steps):
         smp.ctx.sd_set_seed(cfg.seed + s)
-        smp.run(ids, reset_counters=False, **run_kw)
+        run(ids, reset_counters=False, **run_kw)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     counters = smp.buf.counters.tolist()
@@ -308,11 +316,12 @@ def main():
                     help="frozen (default, the benchmark's drafter); independent: a cheaper network of the same "
                          "family called at every window position; efficient_frozen: frozen on the prediction "
                          "carried over from the previous window, one batched target call per window (c1-c4)")
-    ap.add_argument("--loop", default=None, choices=["eager", "multi", "graph"],
+    ap.add_argument("--loop", default=None, choices=["eager", "multi", "graph", "fused"],
                     help="window loop: eager = one host readback of the batch size per window; multi = batch size kept "
                          "on the device, --windows-per-sync windows per readback; graph = multi with window + advance "
-                         "replayed from a HIP graph.  Default: graph for c1, multi for c2, c5 and phi4 (whichever measured "
-                         "faster), eager for c3 and c4 (windows of milliseconds)")
+                         "replayed from a HIP graph; fused (c5, phi4) = every chain's windows back to back in one launch "
+                         "(sd_langevin_run: bit-identical results, no compaction needed).  Default: graph for c1, multi for "
+                         "c2, fused for c5 and phi4 (whichever measured faster), eager for c3 and c4 (windows of milliseconds)")
     ap.add_argument("--windows-per-sync", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
@@ -337,7 +346,9 @@ def main():
     steps = args.steps if args.steps is not None else {"c1": 20, "c2": 10, "c3": 3, "c4": 3, "c5": 2, "phi4": 3}[cfg.name]
     if args.drafter != "frozen" and cfg.kind in ("langevin", "phi4"):
         raise SystemExit("bench.py: the drafter variants are built for the diffusion workloads c1-c4")
-    loop = args.loop or ({"c1": "graph", "c2": "multi", "c5": "multi", "phi4": "multi"}.get(cfg.name, "eager")
+    if args.loop == "fused" and cfg.kind not in ("langevin", "phi4"):
+        raise SystemExit("bench.py: --loop fused is the one-launch form of the Langevin workloads (c5, phi4)")
+    loop = args.loop or ({"c1": "graph", "c2": "multi", "c5": "fused", "phi4": "fused"}.get(cfg.name, "eager")
                          if args.drafter == "frozen" else "eager")
     elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages, args.drafter, loop,
                                                        args.windows_per_sync)
@@ -355,8 +366,9 @@ def main():
                    "chain_steps_T": cfg.T, "drafter": args.drafter, "seed": cfg.seed, "window_loop": loop,
                    "step_definition": "one full sampler pass: all chains from step 0 to T"},
         "mean_accepted_draft_length": round(counters[0] / max(1, counters[1]), 4),
-        "windows_per_step": round(counters[3] / steps, 2),
-        "ms_per_window": round(1e3 * elapsed / max(1, counters[3]), 4),
+        # one launch per pass with --loop fused: a "window" is then the mean number of windows per chain
+        "windows_per_step": round((counters[1] / cfg.B if loop == "fused" else counters[3]) / steps, 2),
+        "ms_per_window": round(1e3 * elapsed / max(1, counters[1] / cfg.B if loop == "fused" else counters[3]), 4),
         "rejections_per_chain_window": round(counters[2] / max(1, counters[1]), 4),
         "target_rows_evaluated": counters[4],
         "roofline": roofline,

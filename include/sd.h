@@ -206,6 +206,27 @@ int sd_langevin_window_phi4(sd_ctx* ctx, int32_t B, const float* x, const int32_
                             float* x_out, int32_t* adv, uint8_t* rejected, float* logratio,
                             float* logu, void* stream);
 
+/* The while-loop of the Langevin algorithm for each chain in one launch: up to max_windows (>= 2) windows
+ * back to back per chain, each exactly what sd_langevin_window (or _phi4) computes, followed by what
+ * sd_advance does to that chain (n += adv; stop at n = T) -- without the compaction, which only the
+ * launch-per-window loop needs.  Chains do not interact in this algorithm (Sec. 5: each chain runs its
+ * own draft-and-verify loop), so nothing forces them to step window by window together: a chain keeps its
+ * state on chip from one window to the next, and no chain waits for the longest window of the batch.
+ * Between two windows the state passes through fp32 as it does between two calls, so results equal the
+ * window + advance loop bit for bit.
+ * in : x [B,d], n [B] (start steps), chain_id [B]; the energy's parameters as in the window calls   (dev)
+ * out: x_out [B,d] and n_out [B], row b = chain b of the input (x_out may be x, n_out may be n);
+ *      counters: dev int64[5] or NULL, accumulated as in sd_advance: {sum adv, chain-windows, rejections,
+ *      launches (+1), sum Kt}.
+ * sd_langevin_run serves d <= 1024 (SD_ERR_UNSUPPORTED above: use the window loop); ordering of calls on one
+ * context as for sd_langevin_window. */
+int sd_langevin_run(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n, const int64_t* chain_id,
+                    const float* means, const float* logw, float comp_std, int32_t M, float gamma,
+                    int32_t max_windows, float* x_out, int32_t* n_out, int64_t* counters, void* stream);
+int sd_langevin_run_phi4(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
+                         const int64_t* chain_id, int32_t L, float beta, float gamma, int32_t max_windows,
+                         float* x_out, int32_t* n_out, int64_t* counters, void* stream);
+
 /* Text of the last error on this context (or of the last failed sd_create when ctx is NULL). */
 const char* sd_last_error(const sd_ctx* ctx);
 

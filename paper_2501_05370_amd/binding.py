@@ -56,6 +56,10 @@ _SIGNATURES = {
                                    c_float, c_int32, c_float] + [c_void_p] * 6),
     "sd_langevin_window_phi4": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int32, c_float, c_float]
                                 + [c_void_p] * 6),
+    "sd_langevin_run": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                c_float, c_int32, c_float, c_int32] + [c_void_p] * 4),
+    "sd_langevin_run_phi4": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int32, c_float, c_float,
+                                     c_int32] + [c_void_p] * 4),
     "sd_last_error": (c_char_p, [c_void_p]),
     # sdden.h
     "sdden_gmm_create": (c_int, [c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_int32, c_void_p,
@@ -253,6 +257,22 @@ class Context:
             _dev(adv, torch.int32, "adv"), _dev(rejected, torch.uint8, "rejected", True),
             _dev(logratio, torch.float32, "logratio", True), _dev(logu, torch.float32, "logu", True),
             _stream()), "sd_langevin_window_phi4")
+
+    def sd_langevin_run(self, B, x, n, chain_id, means, logw, comp_std, M, gamma, max_windows, x_out, n_out,
+                        counters=None):
+        self._check(self._lib.sd_langevin_run(
+            self._h, B, _dev(x, torch.float32, "x"), _dev(n, torch.int32, "n"),
+            _dev(chain_id, torch.int64, "chain_id"), _dev(means, torch.float32, "means"),
+            _dev(logw, torch.float32, "logw"), comp_std, M, gamma, max_windows,
+            _dev(x_out, torch.float32, "x_out"), _dev(n_out, torch.int32, "n_out"),
+            _dev(counters, torch.int64, "counters", True), _stream()), "sd_langevin_run")
+
+    def sd_langevin_run_phi4(self, B, x, n, chain_id, L, beta, gamma, max_windows, x_out, n_out, counters=None):
+        self._check(self._lib.sd_langevin_run_phi4(
+            self._h, B, _dev(x, torch.float32, "x"), _dev(n, torch.int32, "n"),
+            _dev(chain_id, torch.int64, "chain_id"), L, beta, gamma, max_windows,
+            _dev(x_out, torch.float32, "x_out"), _dev(n_out, torch.int32, "n_out"),
+            _dev(counters, torch.int64, "counters", True), _stream()), "sd_langevin_run_phi4")
 
 
 class Denoiser:

@@ -39,6 +39,9 @@ struct LangevinArgs {
   float *logratio, *logu;
   const int32_t* active;
   int32_t* queue;       // [2] chain dispenser of the wavefront kernel: next chain, wavefronts that have left
+  int max_windows;      // 1: one window per chain (sd_langevin_window); > 1: windows back to back (sd_langevin_run)
+  int32_t* n_out;       // run mode: the step each chain reached
+  unsigned long long* counters;   // run mode, optional: sum adv, chain-windows, rejections, launches, sum Kt
   int B, d, K, T, M;
   uint64_t seed;
   double gamma, inv_s2, inv_tau;
@@ -260,7 +263,7 @@ __device__ __forceinline__ double readlane_f64(double v, int src_lane) {
 
 // WHOLE: d is a multiple of 4, so a group of four coordinates is inside d or outside it as a whole (one mask
 // per group instead of four).
-template <int CPT, bool WHOLE>
+template <int CPT, bool WHOLE, bool RUN>
 __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kernel(LangevinArgs p, int dpad) {
   // [kWaveM][dpad] as fp64 (rows beyond M and the pad are 0): converted once here instead of once per use --
   // the logit pass is one FMA per table element, and a conversion beside each would be a fifth of all
@@ -313,13 +316,14 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   // workgroup, not once per four chains) and its wavefronts, independent from here on, take chains one at a
   // time from a counter: a chain's window ends at its first rejection, so the work per chain varies by an
   // order of magnitude and a fixed split would leave most of the chip waiting for the unluckiest wavefront.
+  constexpr bool run = RUN;                                // windows back to back: the chain stays in registers
+  unsigned long long acc_adv = 0, acc_win = 0, acc_rej = 0, acc_kt = 0;   // run mode: this wavefront's share of the counters
   for (;;) {
   int ticket = 0;
   if (lane == 0) ticket = atomicAdd(&p.queue[0], 1);
   const int b = __builtin_amdgcn_readfirstlane(ticket);
   if (b >= Bact) break;
-  const int n = p.n[b];
-  const int Kt = max(0, min(p.K, p.T - n));
+  int n = p.n[b];
   const int64_t id = p.id[b];
 
   bool own[CPT][4];
@@ -393,6 +397,10 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
       for (int e = 0; e < 4; ++e) g[c][e] = (cur[c][e] - bar[c][e]) * inv_s2;
   };
 
+  int Kt = 0, jr = -1;
+  for (int w = 0; w < (RUN ? p.max_windows : 1); ++w) {    // every window advances the chain by at least one step
+  Kt = max(0, min(p.K, p.T - n));
+  if (w > 0 && Kt == 0) break;                             // the chain has reached T
   double g0[CPT][4];
   gradient(g0);
 
@@ -400,7 +408,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   // window; a draw per position would cost every lane a Philox block and an fp64 log each time
   const double lu_mine = lane < Kt ? sdrng::log_uniform(p.seed, id, static_cast<uint32_t>(n + lane + 1)) : 0.0;
 
-  int jr = -1;
+  jr = -1;
   double coef = 0.0;
   double dl[CPT][4];                                       // gradient at the draft, then Delta
   float z[CPT][4];
@@ -455,13 +463,30 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
         cur[c][e] = cur[c][e] - gamma * g0[c][e] + sq2g * static_cast<double>(z[c][e]);
   }
 
-  if (lane == 0) {
-    p.adv[b] = jr >= 0 ? jr + 1 : Kt;
-    if (p.rej) p.rej[b] = jr >= 0 ? 1 : 0;
+  if (run) {
+    // what sd_advance and the next sd_langevin_window would do: the step count moves on and the state passes
+    // through fp32, so a run is bit for bit the window entry point applied again and again
     const int jdone = jr >= 0 ? jr + 1 : Kt;
-    for (int j = jdone; j < p.K; ++j) {
-      if (p.logratio) p.logratio[static_cast<int64_t>(b) * p.K + j] = 0.f;
-      if (p.logu) p.logu[static_cast<int64_t>(b) * p.K + j] = 0.f;
+    n += jdone;
+    acc_adv += jdone; acc_win += 1; acc_rej += jr >= 0 ? 1 : 0; acc_kt += Kt;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) cur[c][e] = static_cast<double>(static_cast<float>(cur[c][e]));
+  }
+  }                                                        // next window of this chain
+
+  if (lane == 0) {
+    if (run) {
+      p.n_out[b] = n;
+    } else {
+      p.adv[b] = jr >= 0 ? jr + 1 : Kt;
+      if (p.rej) p.rej[b] = jr >= 0 ? 1 : 0;
+      const int jdone = jr >= 0 ? jr + 1 : Kt;
+      for (int j = jdone; j < p.K; ++j) {
+        if (p.logratio) p.logratio[static_cast<int64_t>(b) * p.K + j] = 0.f;
+        if (p.logu) p.logu[static_cast<int64_t>(b) * p.K + j] = 0.f;
+      }
     }
   }
 #pragma unroll
@@ -474,6 +499,12 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   }                                                        // next chain of this wavefront
   // The last wavefront to leave rewinds the dispenser for the next launch: every other wavefront drew its
   // final ticket before it counted itself out.
+  if (run && p.counters && lane == 0 && acc_win) {
+    atomicAdd(&p.counters[0], acc_adv);
+    atomicAdd(&p.counters[1], acc_win);
+    atomicAdd(&p.counters[2], acc_rej);
+    atomicAdd(&p.counters[4], acc_kt);
+  }
   if (lane == 0) {
     const int total = static_cast<int>(gridDim.x) * kWaveChains;
     if (atomicAdd(&p.queue[1], 1) == total - 1) {
@@ -483,12 +514,15 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   }
 }
 
-template <int CPT, bool WHOLE>
+// run mode: one launch counts as one entry of the `windows` counter
+__global__ void bump_launches_kernel(unsigned long long* counters) { counters[3] += 1; }
+
+template <int CPT, bool WHOLE, bool RUN>
 hipError_t launch_wave(const LangevinArgs& p, int dpad, hipStream_t st) {
   const size_t shmem = sizeof(double) * kWaveM * static_cast<size_t>(256 * CPT);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&langevin_window_wave_kernel<CPT, WHOLE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&langevin_window_wave_kernel<CPT, WHOLE, RUN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -503,7 +537,7 @@ hipError_t launch_wave(const LangevinArgs& p, int dpad, hipStream_t st) {
   }
   const int groups = (p.B + kWaveChains - 1) / kWaveChains;
   const unsigned grid = static_cast<unsigned>(groups < resident ? groups : resident);
-  hipLaunchKernelGGL((langevin_window_wave_kernel<CPT, WHOLE>), dim3(grid), dim3(64 * kWaveChains), shmem, st, p, dpad);
+  hipLaunchKernelGGL((langevin_window_wave_kernel<CPT, WHOLE, RUN>), dim3(grid), dim3(64 * kWaveChains), shmem, st, p, dpad);
   return hipGetLastError();
 }
 
@@ -529,6 +563,9 @@ struct Phi4Args {
   int B, d, L, K, T;
   uint64_t seed;
   double gamma, beta, inv_tau;
+  int max_windows;                 // sd_langevin_run_phi4: windows per chain at most
+  int32_t* n_out;                  //   the step each chain reached
+  unsigned long long* counters;    //   optional: sum adv, chain-windows, rejections, launches, sum Kt
 };
 
 template <int G>
@@ -659,6 +696,163 @@ __global__ __launch_bounds__(256) void phi4_window_kernel(Phi4Args p) {
     if (own[e]) p.x_out[static_cast<int64_t>(b) * d + 4 * gl + e] = static_cast<float>(cur[e]);
 }
 
+// Windows back to back for the chains of a wavefront (sd_langevin_run_phi4).  A chain's walk is a sequence of
+// steps, each of which costs one gradient at its current state and one draw of noise, whether the step opens a
+// window (the gradient is the frozen one and the position is accepted by construction) or tests a draft (the
+// gradient gives Delta).  So the 64 / G chains of a wavefront stay in lockstep step by step although their
+// windows start and end at different times, and no lane idles before its chain has reached T.
+// Noise and uniforms are keyed by chain and absolute step, so the values are those of the window kernel;
+// the uniforms are drawn G steps at a time and the batch carries over from one window to the next.  At the end
+// of a window the state passes through fp32, as it does between sd_langevin_window_phi4 and the next call:
+// the result is bit for bit that of window + advance repeated.
+template <int G>
+__global__ __launch_bounds__(256) void phi4_run_kernel(Phi4Args p) {
+  constexpr int CPWV = 64 / G;
+  extern __shared__ __align__(16) double sh_x[];     // [256 / G][d]
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int sub = lane / G, gl = lane % G;
+  const int slot = wave * CPWV + sub;
+  const int Bact = p.active ? min(p.B, max(0, *p.active)) : p.B;
+  const int b_raw = blockIdx.x * (4 * CPWV) + slot;
+  const bool valid = b_raw < Bact;
+  const int b = valid ? b_raw : 0;
+  const int d = p.d, L = p.L;
+  int n = valid ? p.n[b] : p.T;
+  const int64_t id = valid ? p.id[b] : 0;
+  const double gamma = p.gamma, beta2 = 2.0 * p.beta;
+  const double sq2g = sqrt(2.0 * gamma), sqg2 = sqrt(0.5 * gamma), inv_sqg2 = 1.0 / sqg2;
+  double* xs = sh_x + static_cast<size_t>(slot) * d;
+
+  bool own[4];
+  int nb[4][4];
+  double cur[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int s = 4 * gl + e;
+    own[e] = s < d;
+    const int sc = own[e] ? s : 0;
+    const int r = sc / L, c = sc % L;
+    nb[e][0] = ((r + L - 1) % L) * L + c;
+    nb[e][1] = ((r + 1) % L) * L + c;
+    nb[e][2] = r * L + (c + L - 1) % L;
+    nb[e][3] = r * L + (c + 1) % L;
+    cur[e] = (valid && own[e]) ? static_cast<double>(p.x[static_cast<int64_t>(b) * d + s]) : 0.0;
+  }
+
+  auto gradient = [&](double g[4]) {               // as in phi4_window_kernel: every lane of the wavefront takes part
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (own[e]) xs[4 * gl + e] = cur[e];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      double v = 0.0;
+      if (own[e]) {
+        const double s4 = xs[nb[e][0]] + xs[nb[e][1]] + xs[nb[e][2]] + xs[nb[e][3]];
+        v = beta2 * (4.0 * cur[e] - s4) + 4.0 * cur[e] * (cur[e] * cur[e] - 1.0);
+      }
+      g[e] = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+
+  int Kt = max(0, min(p.K, p.T - n));
+  int j = 0, windows = 0;
+  bool active = valid && Kt > 0;
+  double g0[4] = {0.0, 0.0, 0.0, 0.0};
+  int lu_base = 0;                                   // first absolute step of the batch of uniforms held in lu_batch
+  bool lu_have = false;
+  double lu_batch = 0.0;
+  unsigned long long acc_adv = 0, acc_win = 0, acc_rej = 0, acc_kt = 0;
+
+  // Ends: a step moves every active chain forward by one position, a window of Kt positions ends after at
+  // most Kt steps and advances n by at least 1, and a chain stops at n = T or after max_windows windows.
+  while (__ballot(active) != 0ull) {
+    double g[4];
+    gradient(g);
+    if (active) {                                    // the lanes of a chain agree
+      const int k1 = n + j + 1;                      // absolute step this position produces
+      float z[4];
+      sdrng::normal4(p.seed, id, static_cast<uint32_t>(k1), sdrng::kStreamNoise, static_cast<uint32_t>(gl), z);
+      bool ended = false, rejected = false;
+      if (j == 0) {                                  // window start: this gradient is the frozen one
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          g0[e] = g[e];
+          if (own[e]) cur[e] = cur[e] - gamma * g0[e] + sq2g * static_cast<double>(z[e]);
+        }
+      } else {
+        if (!lu_have || k1 - lu_base >= G) {
+          lu_base = k1;
+          lu_have = true;
+          lu_batch = sdrng::log_uniform(p.seed, id, static_cast<uint32_t>(k1 + gl));
+        }
+        const double lu = __shfl(lu_batch, sub * G + (k1 - lu_base), 64);
+        double dl[4], a1 = 0.0, a2 = 0.0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          dl[e] = own[e] ? sqg2 * (g[e] - g0[e]) : 0.0;
+          a1 = fma(static_cast<double>(z[e]), dl[e], a1);
+          a2 = fma(dl[e], dl[e], a2);
+        }
+        const double S1 = group_sum_f64<G>(a1), S2 = group_sum_f64<G>(a2);
+        const double lr = (-S1 - 0.5 * S2) * p.inv_tau;
+        rejected = !(S2 == 0.0 || lu <= fmin(0.0, lr));
+        const double coef = S2 > 0.0 ? S1 / S2 : 0.0;
+        if (rejected) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (own[e])
+              cur[e] = cur[e] - gamma * (g0[e] + dl[e] * inv_sqg2) + sq2g * (static_cast<double>(z[e]) - 2.0 * coef * dl[e]);
+          ended = true;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (own[e]) cur[e] = cur[e] - gamma * g0[e] + sq2g * static_cast<double>(z[e]);
+        }
+      }
+      ++j;
+      if (j == Kt) ended = true;
+      if (ended) {
+        n += j;
+        acc_adv += j; acc_win += 1; acc_rej += rejected ? 1 : 0; acc_kt += Kt;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cur[e] = static_cast<double>(static_cast<float>(cur[e]));
+        ++windows;
+        j = 0;
+        Kt = max(0, min(p.K, p.T - n));
+        active = Kt > 0 && windows < p.max_windows;
+      }
+    }
+  }
+
+  if (!valid) return;
+  if (gl == 0) {
+    p.n_out[b] = n;
+    if (p.counters && acc_win) {
+      atomicAdd(&p.counters[0], acc_adv);
+      atomicAdd(&p.counters[1], acc_win);
+      atomicAdd(&p.counters[2], acc_rej);
+      atomicAdd(&p.counters[4], acc_kt);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (own[e]) p.x_out[static_cast<int64_t>(b) * d + 4 * gl + e] = static_cast<float>(cur[e]);
+}
+
+template <int G>
+hipError_t launch_phi4_run(const Phi4Args& p, hipStream_t st) {
+  constexpr int chains_per_wg = 256 / G;
+  const size_t shmem = sizeof(double) * static_cast<size_t>(chains_per_wg) * p.d;
+  const unsigned grid = static_cast<unsigned>((p.B + chains_per_wg - 1) / chains_per_wg);
+  hipLaunchKernelGGL(phi4_run_kernel<G>, dim3(grid), dim3(256), shmem, st, p);
+  return hipGetLastError();
+}
+
 template <int G>
 hipError_t launch_phi4(const Phi4Args& p, hipStream_t st) {
   constexpr int chains_per_wg = 256 / G;
@@ -666,6 +860,68 @@ hipError_t launch_phi4(const Phi4Args& p, hipStream_t st) {
   const unsigned grid = static_cast<unsigned>((p.B + chains_per_wg - 1) / chains_per_wg);
   hipLaunchKernelGGL(phi4_window_kernel<G>, dim3(grid), dim3(256), shmem, st, p);
   return hipGetLastError();
+}
+
+}  // namespace
+
+namespace {
+
+// Shared by sd_langevin_window (max_windows = 1) and sd_langevin_run.
+int langevin_launch(const char* who, sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
+                    const int64_t* chain_id, const float* means, const float* logw, float comp_std, int32_t M,
+                    float gamma, float* x_out, int32_t* adv, uint8_t* rejected, float* logratio, float* logu,
+                    int32_t max_windows, int32_t* n_out, int64_t* counters, void* stream) {
+  if (M > 16)
+    return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "%s: at most 16 mixture components (M=%d)", who, M);
+  const int groups = (ctx->d + 3) / 4;
+  const int cpt = (groups + kThreads - 1) / kThreads;
+  if (cpt > 4)
+    return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "%s: d=%d exceeds the register-resident limit of %d", who,
+                     ctx->d, 4 * 4 * kThreads);
+  LangevinArgs p;
+  p.x = x; p.n = n; p.id = chain_id; p.means = means; p.logw = logw; p.x_out = x_out; p.adv = adv;
+  p.rej = rejected; p.logratio = logratio; p.logu = logu; p.active = ctx->active; p.queue = ctx->dev_queue;
+  p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.M = M; p.seed = ctx->seed;
+  p.gamma = gamma; p.inv_s2 = 1.0 / (static_cast<double>(comp_std) * comp_std); p.inv_tau = 1.0 / ctx->tau;
+  p.max_windows = max_windows; p.n_out = n_out; p.counters = reinterpret_cast<unsigned long long*>(counters);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int dpad = 4 * groups;
+  if (dpad <= 1024) {                       // a wavefront per chain, means in LDS (16 rows of doubles, <= 128 KiB)
+    hipError_t e;
+    const bool whole = ctx->d % 4 == 0;
+    const int sel = ((groups + 63) / 64 - 1) * 4 + (whole ? 2 : 0) + (max_windows > 1 ? 1 : 0);
+    switch (sel) {
+      case 0: e = launch_wave<1, false, false>(p, dpad, st); break;
+      case 1: e = launch_wave<1, false, true>(p, dpad, st); break;
+      case 2: e = launch_wave<1, true, false>(p, dpad, st); break;
+      case 3: e = launch_wave<1, true, true>(p, dpad, st); break;
+      case 4: e = launch_wave<2, false, false>(p, dpad, st); break;
+      case 5: e = launch_wave<2, false, true>(p, dpad, st); break;
+      case 6: e = launch_wave<2, true, false>(p, dpad, st); break;
+      case 7: e = launch_wave<2, true, true>(p, dpad, st); break;
+      case 8: e = launch_wave<3, false, false>(p, dpad, st); break;
+      case 9: e = launch_wave<3, false, true>(p, dpad, st); break;
+      case 10: e = launch_wave<3, true, false>(p, dpad, st); break;
+      case 11: e = launch_wave<3, true, true>(p, dpad, st); break;
+      case 12: e = launch_wave<4, false, false>(p, dpad, st); break;
+      case 13: e = launch_wave<4, false, true>(p, dpad, st); break;
+      case 14: e = launch_wave<4, true, false>(p, dpad, st); break;
+      default: e = launch_wave<4, true, true>(p, dpad, st); break;
+    }
+    if (e != hipSuccess) return sdi::fail(ctx->err, SD_ERR_HIP, "%s: %s", who, hipGetErrorString(e));
+    if (max_windows > 1 && counters) hipLaunchKernelGGL(bump_launches_kernel, dim3(1), dim3(1), 0, st, p.counters);
+    return SD_OK;
+  }
+  if (max_windows > 1)
+    return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "%s: d=%d is above the 1024 the back-to-back form serves", who, ctx->d);
+  const dim3 grid(static_cast<unsigned>(B)), block(kThreads);
+  switch (cpt) {
+    case 1: hipLaunchKernelGGL((langevin_window_kernel<1, 16>), grid, block, 0, st, p); break;
+    case 2: hipLaunchKernelGGL((langevin_window_kernel<2, 16>), grid, block, 0, st, p); break;
+    default: hipLaunchKernelGGL((langevin_window_kernel<4, 16>), grid, block, 0, st, p); break;
+  }
+  SD_HIP_TRY(ctx->err, hipGetLastError());
+  return SD_OK;
 }
 
 }  // namespace
@@ -679,40 +935,20 @@ extern "C" int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const 
       (B > 0 && (!x || !n || !chain_id || !means || !logw || !x_out || !adv)))
     return sdi::fail(ctx->err, SD_ERR_ARG, "sd_langevin_window: bad argument");
   if (B == 0) return SD_OK;
-  if (M > 16)
-    return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_langevin_window: at most 16 mixture components (M=%d)", M);
-  const int groups = (ctx->d + 3) / 4;
-  const int cpt = (groups + kThreads - 1) / kThreads;
-  if (cpt > 4)
-    return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_langevin_window: d=%d exceeds the register-resident limit of %d",
-                     ctx->d, 4 * 4 * kThreads);
-  LangevinArgs p;
-  p.x = x; p.n = n; p.id = chain_id; p.means = means; p.logw = logw; p.x_out = x_out; p.adv = adv;
-  p.rej = rejected; p.logratio = logratio; p.logu = logu; p.active = ctx->active; p.queue = ctx->dev_queue;
-  p.B = B; p.d = ctx->d; p.K = ctx->K; p.T = ctx->T; p.M = M; p.seed = ctx->seed;
-  p.gamma = gamma; p.inv_s2 = 1.0 / (static_cast<double>(comp_std) * comp_std); p.inv_tau = 1.0 / ctx->tau;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const int dpad = 4 * groups;
-  if (dpad <= 1024) {                       // a wavefront per chain, means in LDS (16 rows of doubles, <= 128 KiB)
-    hipError_t e;
-    const bool whole = ctx->d % 4 == 0;
-    switch ((groups + 63) / 64) {
-      case 1: e = whole ? launch_wave<1, true>(p, dpad, st) : launch_wave<1, false>(p, dpad, st); break;
-      case 2: e = whole ? launch_wave<2, true>(p, dpad, st) : launch_wave<2, false>(p, dpad, st); break;
-      case 3: e = whole ? launch_wave<3, true>(p, dpad, st) : launch_wave<3, false>(p, dpad, st); break;
-      default: e = whole ? launch_wave<4, true>(p, dpad, st) : launch_wave<4, false>(p, dpad, st); break;
-    }
-    if (e != hipSuccess) return sdi::fail(ctx->err, SD_ERR_HIP, "sd_langevin_window: %s", hipGetErrorString(e));
-    return SD_OK;
-  }
-  const dim3 grid(static_cast<unsigned>(B)), block(kThreads);
-  switch (cpt) {
-    case 1: hipLaunchKernelGGL((langevin_window_kernel<1, 16>), grid, block, 0, st, p); break;
-    case 2: hipLaunchKernelGGL((langevin_window_kernel<2, 16>), grid, block, 0, st, p); break;
-    default: hipLaunchKernelGGL((langevin_window_kernel<4, 16>), grid, block, 0, st, p); break;
-  }
-  SD_HIP_TRY(ctx->err, hipGetLastError());
-  return SD_OK;
+  return langevin_launch("sd_langevin_window", ctx, B, x, n, chain_id, means, logw, comp_std, M, gamma, x_out, adv,
+                         rejected, logratio, logu, 1, nullptr, nullptr, stream);
+}
+
+extern "C" int sd_langevin_run(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n, const int64_t* chain_id,
+                               const float* means, const float* logw, float comp_std, int32_t M, float gamma,
+                               int32_t max_windows, float* x_out, int32_t* n_out, int64_t* counters, void* stream) {
+  if (!ctx) return SD_ERR_ARG;
+  if (B < 0 || M <= 0 || !(comp_std > 0.f) || !(gamma > 0.f) || max_windows < 2 ||
+      (B > 0 && (!x || !n || !chain_id || !means || !logw || !x_out || !n_out)))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_langevin_run: bad argument (max_windows >= 2)");
+  if (B == 0) return SD_OK;
+  return langevin_launch("sd_langevin_run", ctx, B, x, n, chain_id, means, logw, comp_std, M, gamma, x_out, nullptr,
+                         nullptr, nullptr, nullptr, max_windows, n_out, counters, stream);
 }
 
 extern "C" int sd_langevin_window_phi4(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
@@ -730,6 +966,7 @@ extern "C" int sd_langevin_window_phi4(sd_ctx* ctx, int32_t B, const float* x, c
   p.x = x; p.n = n; p.id = chain_id; p.x_out = x_out; p.adv = adv; p.rej = rejected; p.logratio = logratio; p.logu = logu;
   p.active = ctx->active; p.B = B; p.d = ctx->d; p.L = L; p.K = ctx->K; p.T = ctx->T; p.seed = ctx->seed;
   p.gamma = gamma; p.beta = beta; p.inv_tau = 1.0 / ctx->tau;
+  p.max_windows = 1; p.n_out = nullptr; p.counters = nullptr;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int groups = (ctx->d + 3) / 4;
   hipError_t e;
@@ -739,5 +976,36 @@ extern "C" int sd_langevin_window_phi4(sd_ctx* ctx, int32_t B, const float* x, c
   else if (groups <= 32) e = launch_phi4<32>(p, st);
   else e = launch_phi4<64>(p, st);
   if (e != hipSuccess) return sdi::fail(ctx->err, SD_ERR_HIP, "sd_langevin_window_phi4: %s", hipGetErrorString(e));
+  return SD_OK;
+}
+
+extern "C" int sd_langevin_run_phi4(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n, const int64_t* chain_id,
+                                    int32_t L, float beta, float gamma, int32_t max_windows, float* x_out,
+                                    int32_t* n_out, int64_t* counters, void* stream) {
+  if (!ctx) return SD_ERR_ARG;
+  if (B < 0 || L < 3 || !(beta >= 0.f) || !(gamma > 0.f) || max_windows < 2 ||
+      (B > 0 && (!x || !n || !chain_id || !x_out || !n_out)))
+    return sdi::fail(ctx->err, SD_ERR_ARG,
+                     "sd_langevin_run_phi4: bad argument (L >= 3, beta >= 0, gamma > 0, max_windows >= 2)");
+  if (L * L != ctx->d)
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_langevin_run_phi4: the context's d=%d is not L*L=%d", ctx->d, L * L);
+  if (ctx->d > 256)
+    return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_langevin_run_phi4: grids up to 16 x 16 (d=%d)", ctx->d);
+  if (B == 0) return SD_OK;
+  Phi4Args p;
+  p.x = x; p.n = n; p.id = chain_id; p.x_out = x_out; p.adv = nullptr; p.rej = nullptr; p.logratio = nullptr; p.logu = nullptr;
+  p.active = ctx->active; p.B = B; p.d = ctx->d; p.L = L; p.K = ctx->K; p.T = ctx->T; p.seed = ctx->seed;
+  p.gamma = gamma; p.beta = beta; p.inv_tau = 1.0 / ctx->tau;
+  p.max_windows = max_windows; p.n_out = n_out; p.counters = reinterpret_cast<unsigned long long*>(counters);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int groups = (ctx->d + 3) / 4;
+  hipError_t e;
+  if (groups <= 4) e = launch_phi4_run<4>(p, st);
+  else if (groups <= 8) e = launch_phi4_run<8>(p, st);
+  else if (groups <= 16) e = launch_phi4_run<16>(p, st);
+  else if (groups <= 32) e = launch_phi4_run<32>(p, st);
+  else e = launch_phi4_run<64>(p, st);
+  if (e != hipSuccess) return sdi::fail(ctx->err, SD_ERR_HIP, "sd_langevin_run_phi4: %s", hipGetErrorString(e));
+  if (counters) hipLaunchKernelGGL(bump_launches_kernel, dim3(1), dim3(1), 0, st, p.counters);
   return SD_OK;
 }

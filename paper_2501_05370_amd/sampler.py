@@ -302,6 +302,18 @@ class LangevinSampler(_SamplerBase):
                                         self.M, self.gamma, b.y_out, b.adv, b.rejected, logratio, logu)
 
 
+    def run_fused(self, chain_ids: torch.Tensor, reset_counters: bool = True):
+        """All chains to step T in one launch (``sd_langevin_run``): same results as ``run``, bit for bit.
+        Returns (final states in the order of chain_ids, counters)."""
+        B = self.start(chain_ids, reset_counters)
+        b = self.buf
+        if B > 0:
+            with self.timer.stage("langevin_run", B):
+                self.ctx.sd_langevin_run(B, b.y, b.n, b.chain_id, self.means, self.logw, self.comp_std, self.M,
+                                         self.gamma, max(2, self.ctx.T), b.y_out, b.n, b.counters)
+        return b.y_out[:B], b.counters.tolist()
+
+
 class Phi4LangevinSampler(_SamplerBase):
     """Speculative unadjusted Langevin on the phi^4 lattice energy: ``sd_langevin_window_phi4`` + ``sd_advance``."""
 
@@ -314,3 +326,13 @@ class Phi4LangevinSampler(_SamplerBase):
         with self.timer.stage("langevin_window", B):
             self.ctx.sd_langevin_window_phi4(B, b.y, b.n, b.chain_id, self.L, self.beta,
                                              self.gamma, b.y_out, b.adv, b.rejected, logratio, logu)
+
+    def run_fused(self, chain_ids: torch.Tensor, reset_counters: bool = True):
+        """All chains to step T in one launch (``sd_langevin_run_phi4``): same results as ``run``, bit for bit."""
+        B = self.start(chain_ids, reset_counters)
+        b = self.buf
+        if B > 0:
+            with self.timer.stage("langevin_run", B):
+                self.ctx.sd_langevin_run_phi4(B, b.y, b.n, b.chain_id, self.L, self.beta, self.gamma,
+                                              max(2, self.ctx.T), b.y_out, b.n, b.counters)
+        return b.y_out[:B], b.counters.tolist()

@@ -207,3 +207,34 @@ def test_phi4_full_size_sampled_chains():
     assert Ba == int((n_next < T).sum())
     assert np.array_equal(host(b.n)[:Ba], n_next[n_next < T])
     assert np.array_equal(host(b.chain_id)[:Ba], ids[n_next < T])
+
+
+@pytest.mark.parametrize("name,T", [("c5", 160), ("phi4", 400)])
+def test_langevin_full_size_run_equals_the_window_loop(name, T):
+    """The one-launch form (sd_langevin_run / sd_langevin_run_phi4) that bench.py times for c5 and phi4, at
+    the benchmark's batch and state size (the chain length is cut to keep the test short): final states
+    and counters equal those of the launch-per-window loop bit for bit; sampled chains are compared with the
+    oracle's sampler, which carries its states in fp64 (tolerance as in the small free-run tests)."""
+    from oracle.langevin import Phi4Energy
+    from paper_2501_05370_amd.runner import make_sampler
+    cfg = W.make_config(name, T=T)
+    B = cfg.B
+    ids = torch.arange(B, dtype=torch.int64, device="cuda")
+    smp = make_sampler(cfg)
+    out, cw = smp.run(ids, windows_per_sync=4)
+    xw = out[:B].clone()
+    smp2 = make_sampler(cfg)
+    out2, cf = smp2.run_fused(ids)
+    assert torch.equal(xw, out2[:B])
+    assert [cf[i] for i in (0, 1, 2, 4)] == [cw[i] for i in (0, 1, 2, 4)] and cf[0] == B * T
+    assert bool((smp2.buf.n[:B] == T).all())
+    sample = np.sort(np.random.default_rng(61).choice(B, 24, replace=False))
+    grad = Phi4Energy(cfg.params.L, cfg.params.beta) if name == "phi4" else GMMScore(cfg.params)
+    ref, _, _ = L.ula_sample(grad, len(sample), cfg.d, cfg.K, T, cfg.gamma, seed=cfg.seed,
+                             chain_ids=sample.astype(np.int64))
+    got = host(out2[torch.as_tensor(sample, device="cuda")])
+    err = np.max(np.abs(got - ref), axis=1) / np.maximum(1.0, np.abs(ref).max(axis=1))
+    diverged = int((err > 1e-3).sum())
+    print(f"[{name} one launch, {B} chains, T={T}] counters {cf}; {len(sample)} chains against the oracle: "
+          f"max err {err.max():.2e}, off-path {diverged}")
+    assert diverged <= 2

@@ -202,3 +202,60 @@ def test_phi4_langevin_free_run_and_argument_checks():
         smp.ctx.sd_langevin_window_phi4(4, b.y, b.n, b.chain_id, 7, 100.0, 1e-3, b.y_out, b.adv, b.rejected)
     with pytest.raises(SDError):
         smp.ctx.sd_langevin_window_phi4(4, b.y, b.n, b.chain_id, 8, 100.0, -1.0, b.y_out, b.adv, b.rejected)
+
+
+@pytest.mark.parametrize("B,d,M,K,T", [(300, 200, 4, 8, 60), (64, 1000, 16, 16, 45), (37, 10, 3, 5, 23), (50, 701, 16, 8, 20)])
+def test_langevin_run_equals_the_window_loop_and_the_oracle(B, d, M, K, T):
+    """sd_langevin_run (every chain's windows back to back in one launch) against the launch-per-window
+    loop of the same library, bit for bit, and against the oracle's sampler."""
+    from paper_2501_05370_amd.binding import SDError
+    from paper_2501_05370_amd.sampler import LangevinSampler
+    cfg = W.make_config("c5", B=B, d=d, M=M, K=K, T=T)
+    p = cfg.params
+    ids = torch.arange(B, dtype=torch.int64, device="cuda")
+    outs = []
+    for fused in (False, True):
+        ctx = make_context(cfg.schedule, d, K, seed=5)
+        smp = LangevinSampler(ctx, f32(p.means), f32(p.logw), float(p.stds[0, 0]), cfg.gamma, B)
+        out, counters = smp.run_fused(ids) if fused else smp.run(ids)
+        outs.append((host(out)[:B].copy(), counters, host(smp.buf.n)[:B].copy() if fused else None))
+    (xw, cw, _), (xf, cf, nf) = outs
+    assert np.array_equal(xw, xf)
+    assert [cf[i] for i in (0, 1, 2, 4)] == [cw[i] for i in (0, 1, 2, 4)] and cf[3] == 1
+    assert np.all(nf == T)
+    ref, ocw, orej = L.ula_sample(GMMScore(p), B, d, K, T, cfg.gamma, seed=5)
+    err = np.max(np.abs(xf - ref), axis=1) / np.maximum(1.0, np.abs(ref).max(axis=1))
+    diverged = int((err > 1e-3).sum())
+    print(f"[langevin run d={d}] counters {cf}, oracle chain-windows {ocw} rejections {orej}, off-path {diverged}")
+    assert cf[0] == B * T and diverged <= 1
+    if diverged == 0:
+        assert cf[1] == ocw and cf[2] == orej
+    # a bound on the windows per chain: two windows advance a chain by 2..2K steps, and a second call finishes
+    ctx = make_context(cfg.schedule, d, K, seed=5)
+    smp = LangevinSampler(ctx, f32(p.means), f32(p.logw), float(p.stds[0, 0]), cfg.gamma, B)
+    b = smp.buf
+    smp.start(ids)
+    ctx.sd_langevin_run(B, b.y, b.n, b.chain_id, smp.means, smp.logw, smp.comp_std, M, cfg.gamma, 2, b.y, b.n, b.counters)
+    n2 = host(b.n)[:B]
+    assert np.all(n2 >= min(2, T)) and np.all(n2 <= min(T, 2 * K))
+    ctx.sd_langevin_run(B, b.y, b.n, b.chain_id, smp.means, smp.logw, smp.comp_std, M, cfg.gamma, T, b.y, b.n, b.counters)
+    assert np.array_equal(host(b.y)[:B], xw) and np.all(host(b.n)[:B] == T)
+    with pytest.raises(SDError):
+        ctx.sd_langevin_run(B, b.y, b.n, b.chain_id, smp.means, smp.logw, smp.comp_std, M, cfg.gamma, 1, b.y, b.n, None)
+
+
+@pytest.mark.parametrize("L_,B,K,T", [(8, 300, 20, 50), (4, 70, 6, 30), (16, 40, 12, 40), (5, 33, 7, 25)])
+def test_phi4_langevin_run_equals_the_window_loop(L_, B, K, T):
+    from paper_2501_05370_amd.runner import make_sampler
+    cfg = W.make_config("phi4", B=B, T=T, K=K, d=L_ * L_)
+    ids = torch.arange(B, dtype=torch.int64, device="cuda")
+    smp = make_sampler(cfg)
+    out, cw = smp.run(ids)
+    xw = host(out)[:B].copy()
+    smp2 = make_sampler(cfg)
+    out2, cf = smp2.run_fused(ids)
+    xf = host(out2)[:B].copy()
+    print(f"[phi4 run L={L_}] counters window loop {cw}, one launch {cf}")
+    assert np.array_equal(xw, xf)
+    assert [cf[i] for i in (0, 1, 2, 4)] == [cw[i] for i in (0, 1, 2, 4)] and cf[3] == 1
+    assert np.all(host(smp2.buf.n)[:B] == T)
