@@ -13,36 +13,50 @@ namespace sdrows {
 
 constexpr int kScan = 1024;
 
+constexpr int kScanBatch = 8;      // chunks of kScan rows whose steps are requested together
+
 // rowidx[0..count) = indices r < Ract with krow[r] >= 0, in increasing order; *count = how many.
+// One workgroup walks the rows; it is a chain of global-load round trips unless the loads are batched, so a
+// thread requests its rows of kScanBatch chunks at once and the chunks are then ranked from registers.
 static __global__ __launch_bounds__(kScan) void compact_rows_kernel(const int32_t* __restrict__ krow,
                                                                     int32_t* __restrict__ rowidx,
                                                                     int32_t* __restrict__ count,
                                                                     const int32_t* active,
                                                                     int rows_per_chain, int R) {
-  __shared__ int wave_tot[kScan / 64];
-  __shared__ int sh_base;
+  constexpr int NW = kScan / 64;
+  __shared__ int wave_tot[kScanBatch][NW];
   const int Ract = sdi::active_rows(active, rows_per_chain, R);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) sh_base = 0;
-  __syncthreads();
-  for (int start = 0; start < Ract; start += kScan) {
-    const int r = start + tid;
-    const bool keep = r < Ract && krow[r] >= 0;
-    const unsigned long long m = __ballot(keep);
-    if (lane == 0) wave_tot[wave] = __popcll(m);
-    __syncthreads();
-    int offset = sh_base;
-    for (int w = 0; w < wave; ++w) offset += wave_tot[w];
-    if (keep) rowidx[offset + __popcll(m & ((1ull << lane) - 1ull))] = r;
-    __syncthreads();
-    if (tid == 0) {
-      int tot = 0;
-      for (int w = 0; w < kScan / 64; ++w) tot += wave_tot[w];
-      sh_base += tot;
+  int base = 0;                                    // kept rows before this batch (the same in every thread)
+  for (int start = 0; start < Ract; start += kScan * kScanBatch) {
+    bool keep[kScanBatch];
+#pragma unroll
+    for (int c = 0; c < kScanBatch; ++c) {
+      const int r = start + c * kScan + tid;
+      keep[c] = r < Ract && krow[r] >= 0;
+    }
+    unsigned long long m[kScanBatch];
+#pragma unroll
+    for (int c = 0; c < kScanBatch; ++c) {
+      m[c] = __ballot(keep[c]);
+      if (lane == 0) wave_tot[c][wave] = __popcll(m[c]);
     }
     __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kScanBatch; ++c) {
+      int before = 0, total = 0;                   // kept rows of chunk c in earlier wavefronts / in all
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const int v = wave_tot[c][w];
+        before += w < wave ? v : 0;
+        total += v;
+      }
+      if (keep[c]) rowidx[base + before + __popcll(m[c] & ((1ull << lane) - 1ull))] = start + c * kScan + tid;
+      base += total;
+    }
+    __syncthreads();                               // wave_tot is rewritten by the next batch
   }
-  if (tid == 0) *count = sh_base;
+  if (tid == 0) *count = base;
 }
 
 }  // namespace sdrows
