@@ -5,7 +5,8 @@
 // Same skeleton as the bf16 MLP GEMM: BM x BN x 32 workgroup tile, WM x WN wavefronts of 32x32
 // v_mfma_f32_32x32x2f32 accumulators, K-slices of 32 floats (128 B per row) loaded from global memory
 // straight into LDS (a wavefront load fills 8 rows, lane l landing at byte 16*l, the lane fetching
-// chunk (l%8) ^ (l/8) of its row so that fragment reads are bank-conflict free), an NS-stage LDS
+// chunk (l%8) ^ ((row >> 1) & 7) of its row so that fragment reads are bank-conflict free on the 64-bank
+// LDS: see the bf16 GEMM), an NS-stage LDS
 // ring with a workgroup barrier that leaves loads in flight.
 // Fragments: a lane reads one 16-byte chunk = 4 consecutive k of its row and feeds 4 MFMAs; the two
 // lane halves of an MFMA (k index 0 / 1 of the instruction) read chunks 2m / 2m+1, i.e. MFMA e of
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int half = lane >> 5, l32 = lane & 31;
-  const int lrow = lane >> 3, lchunk = (lane & 7) ^ (lane >> 3);
+  const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);   // (LDS row >> 1) & 7, see above
 
   // source rows of this lane's loads (rows past M / N are clamped: computed, never stored)
   const unsigned char* a_src[APASS];
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   }
 
   const int a_row = (wm * (BM / WM) + l32) * 128, b_row = (wn * (BN / WN) + l32) * 128;
-  const int sw = l32 & 7;
+  const int sw = (l32 >> 1) & 7;
   for (int kt = 0; kt < nk; ++kt) {
     const int s = kt % NS;
     if (kt + NS - 1 < nk) {

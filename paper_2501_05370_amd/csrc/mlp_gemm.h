@@ -6,8 +6,12 @@
 // into LDS (global_load_lds_dwordx4): no staging registers and no LDS store instructions.  One
 // wavefront load fills 1 KiB of LDS = 8 rows of a 64-element slice, lane l landing at byte 16*l;
 // bank conflicts are avoided by permuting which 16-byte chunk of its row a lane fetches
-// (chunk ^ row%8) instead of padding rows, so the 16-byte fragment reads of any 8 consecutive
-// rows cover all 32 banks.  NS LDS stages form a ring: up to NS-1 slices stream in while the
+// (chunk ^ ((row >> 1) & 7), row = the row's place in the LDS tile) instead of padding rows.  The LDS of
+// gfx950 serves a 128-bit read 16 lanes at a time out of 64 four-byte banks, so the 16-byte reads of 16
+// consecutive rows at one k-chunk must fall on 16 different places modulo 256 bytes: two rows are 256
+// bytes, so the row's parity picks the half and (row >> 1) & 7 has to run through all eight chunks.
+// The permutation chunk ^ (row & 7), which is the one for 32 banks, reads at half the rate here
+// (measured: 123 against 224 bytes per clock and CU, SQ_LDS_BANK_CONFLICT equal to the busy cycles).  NS LDS stages form a ring: up to NS-1 slices stream in while the
 // current one feeds the MFMAs.  The per-slice workgroup barrier is a bare s_barrier behind
 // s_waitcnt vmcnt(n): __syncthreads() would drain every outstanding load and empty the ring.
 // The 256 x 256 tile fills LDS with two stages; the 128 x 128 tile used for few rows runs four,
@@ -101,8 +105,8 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   const int half = lane >> 5, l32 = lane & 31;
   const int Kd = p.Kdim;
 
-  // lane's source: row (8*group + lane/8), 16-byte chunk (lane%8) ^ (lane/8)
-  const int lrow = lane >> 3, lchunk = (lane & 7) ^ (lane >> 3);
+  // lane's source: row (8*group + lane/8), 16-byte chunk (lane%8) ^ ((row >> 1) & 7); the group's parity is the wavefront's
+  const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);   // (LDS row >> 1) & 7, see above
   const unsigned char* a_lane = reinterpret_cast<const unsigned char*>(p.A) +
                                 (static_cast<size_t>(tile_m) * BM + 8 * wave + lrow) * Kd * 2 + 16 * lchunk;
   const unsigned char* b_lane = reinterpret_cast<const unsigned char*>(p.Bt) +
@@ -153,9 +157,9 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
 #pragma unroll
   for (int k = 0; k < NS - 1; ++k)
     if (k < nk) MLPGEMM_FETCH(k, k * BK);
-  // fragment addressing: row r, chunk c -> r*128 + ((c ^ (r & 7)) << 4); r & 7 == l32 & 7 for all tiles
+  // fragment addressing: row r, chunk c -> r*128 + ((c ^ ((r >> 1) & 7)) << 4); tiles start at multiples of 32 rows
   const int a_row = (wm * (BM / WM) + l32) * 128, b_row = (wn * (BN / WN) + l32) * 128;
-  const int sw = l32 & 7;
+  const int sw = (l32 >> 1) & 7;
   for (int kt = 0; kt < nk; ++kt) {
     const int s = kt % NS;
     // slice kt has landed once only the NS-2 younger slices are outstanding; past the barrier every
@@ -273,7 +277,7 @@ __global__ __launch_bounds__(512) void kernel_hs(Args p) {
   const int wm = wave / WN, wn = wave % WN;
   const int half = lane >> 5, l32 = lane & 31;
   const int Kd = p.Kdim;
-  const int lrow = lane >> 3, lchunk = (lane & 7) ^ (lane >> 3);
+  const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);   // (LDS row >> 1) & 7, see above
   const unsigned char* b_lane = reinterpret_cast<const unsigned char*>(p.Bt) +
                                 (static_cast<size_t>(tile_n) * BN + 8 * wave + lrow) * Kd * 2 + 16 * lchunk;
   const size_t pass_stride = static_cast<size_t>(8 * NW) * Kd * 2;
@@ -318,7 +322,7 @@ __global__ __launch_bounds__(512) void kernel_hs(Args p) {
   } while (0)
 
   // fragment addresses as LDS byte offsets: row base + swizzled chunk of k-step kk; tiles and stages are immediates
-  const int sw = l32 & 7;
+  const int sw = (l32 >> 1) & 7;
   const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
   uint32_t a_ad[4], b_ad[4];
 #pragma unroll
