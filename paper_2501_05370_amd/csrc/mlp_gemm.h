@@ -82,6 +82,7 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int APASS = BM / 8 / NW, BPASS = BN / 8 / NW;    // wavefront loads per K-slice
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "row groups must divide evenly");
+  static_assert(NW % 2 == 0, "the chunk permutation takes the parity of a row group from the wavefront index");
   extern __shared__ __align__(1024) unsigned char smem[];
   unsigned char* As = smem;                                  // [NS][BM][128 B]
   unsigned char* Bs = smem + NS * BM * 128;                  // [NS][BN][128 B]
