@@ -8,12 +8,13 @@
 //   reject:  x_out = y~_{j-1} - gamma grad E(y~_{j-1}) + sqrt(2 gamma) (z - 2 (z.Delta/|Delta|^2) Delta)
 // with E(x) = -log sum_m w_m N(x; mu_m, s^2 I), grad E = (x - sum_m r_m(x) mu_m) / s^2.
 //
-// One workgroup per chain.  A thread owns CPT groups of four consecutive coordinates (= one
-// Philox block each), keeps the window state, the frozen gradient and its slice of the mixture
-// means in registers, and walks the window positions in order; because the whole chain lives in
-// one workgroup the walk simply stops at the first rejection, so no work is spent on drafts
-// that would be discarded.  Per position: 16 logit partial sums and the two dot products are
-// reduced over the workgroup in fp64.
+// Three kernels.  For d <= 1024 a WAVEFRONT owns a chain (langevin_window_wave_kernel, further down); for
+// larger d a workgroup does (langevin_window_kernel, next): a thread owns CPT groups of four consecutive
+// coordinates (= one Philox block each), keeps the window state, the frozen gradient and its slice of
+// the mixture means in registers, and walks the window positions in order; because the whole chain
+// lives in one workgroup the walk simply stops at the first rejection, so no work is spent on drafts
+// that would be discarded.  Per position: 16 logit partial sums and the two dot products are reduced
+// over the workgroup in fp64.  The phi^4 lattice energy has kernels of its own at the end of the file.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -228,12 +229,14 @@ __global__ __launch_bounds__(kThreads) void langevin_window_kernel(LangevinArgs 
 
 // ---------------------------------------------------------------------------------------------
 // One WAVEFRONT per chain (d <= 1024 * CPT/4): no workgroup barrier on the walk at all.
-// A lane owns CPT groups of four coordinates; the mixture means sit in LDS once per workgroup
-// (kWaveChains chains share them).  Logits use  log w_m + (x.mu_m - |mu_m|^2/2)/s^2  (the |x|^2 term
-// cancels in the softmax), so a position costs two passes over the means: 16 dot products and the
+// A lane owns CPT groups of four coordinates; the mixture means sit in LDS as fp64, once per workgroup
+// (its kWaveChains wavefronts share them; the workgroups stay resident for the whole launch and their
+// wavefronts draw chains from a counter).  Logits use  log w_m + (x.mu_m - |mu_m|^2/2)/s^2  (the |x|^2
+// term cancels in the softmax), so a position costs two passes over the means: 16 dot products and the
 // responsibility-weighted mean.  The 16 per-lane partial dot products are reduced with a transposed
-// butterfly (values are exchanged in halves, 17 shuffles instead of 96); responsibilities are then
-// broadcast through scalar registers.
+// butterfly (values are exchanged in halves, 17 exchanges instead of 96, all of them DPP moves or row
+// swaps in the vector ALU); responsibilities are then broadcast through scalar registers.
+// RUN: the chain's windows follow each other inside the kernel (sd_langevin_run).
 // ---------------------------------------------------------------------------------------------
 constexpr int kWaveChains = 8;             // chains (wavefronts) per workgroup: one workgroup fills a CU at 2 per SIMD
 constexpr int kWaveM = 16;                 // components handled by the transposed reduction
