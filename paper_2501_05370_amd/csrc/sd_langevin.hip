@@ -403,7 +403,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
   int Kt = 0, jr = -1;
   for (int w = 0; w < (RUN ? p.max_windows : 1); ++w) {    // every window advances the chain by at least one step
   Kt = max(0, min(p.K, p.T - n));
-  if (w > 0 && Kt == 0) break;                             // the chain has reached T
+  if ((RUN || w > 0) && Kt == 0) break;                    // the chain has reached T (a chain handed over at T: no window)
   double g0[CPT][4];
   gradient(g0);
 

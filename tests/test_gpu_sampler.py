@@ -242,6 +242,13 @@ def test_langevin_run_equals_the_window_loop_and_the_oracle(B, d, M, K, T):
     assert np.array_equal(host(b.y)[:B], xw) and np.all(host(b.n)[:B] == T)
     with pytest.raises(SDError):
         ctx.sd_langevin_run(B, b.y, b.n, b.chain_id, smp.means, smp.logw, smp.comp_std, M, cfg.gamma, 1, b.y, b.n, None)
+    # chains handed over at step T are left as they are and count no window
+    before = b.counters.tolist()
+    xo = torch.zeros_like(b.y)
+    ctx.sd_langevin_run(B, b.y, b.n, b.chain_id, smp.means, smp.logw, smp.comp_std, M, cfg.gamma, 5, xo, b.n, b.counters)
+    after = b.counters.tolist()
+    assert torch.equal(xo[:B], b.y[:B]) and np.all(host(b.n)[:B] == T)
+    assert [after[i] for i in (0, 1, 2, 4)] == [before[i] for i in (0, 1, 2, 4)]
 
 
 @pytest.mark.parametrize("L_,B,K,T", [(8, 300, 20, 50), (4, 70, 6, 30), (16, 40, 12, 40), (5, 33, 7, 25)])
