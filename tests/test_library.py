@@ -71,3 +71,20 @@ def test_denoiser_create_validates_arguments():
     assert lib.sdden_gmm_create(2, 3, mu.ctypes.data, sd.ctypes.data, lw.ctypes.data, 4, ab.ctypes.data,
                                 ctypes.byref(h)) == -1      # stds must be positive
     assert b"stds" in lib.sdden_last_error(None)
+
+
+def test_bench_refuses_more_than_one_gpu_and_needs_the_library():
+    """bench.py is a one-GPU program: --gpus 2 ends with a message before anything touches a device; and the
+    product path has no CPU stand-in (without a GPU the run ends with an error, not with oracle numbers)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120, cwd=root)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "c1", "--no-cpu-baseline"],
+                           capture_output=True, text=True, timeout=300, cwd=root)
+        assert r.returncode != 0 and '"metric"' not in r.stdout
