@@ -321,7 +321,7 @@ def main():
                          "on the device, --windows-per-sync windows per readback; graph = multi with window + advance "
                          "replayed from a HIP graph; fused (c5, phi4) = every chain's windows back to back in one launch "
                          "(sd_langevin_run: bit-identical results, no compaction needed).  Default: graph for c1, multi for "
-                         "c2, fused for c5 and phi4 (whichever measured faster), eager for c3 and c4 (windows of milliseconds)")
+                         "c2 and c3, fused for c5 and phi4 (whichever measured faster), eager for c4 (windows of 2 ms: no difference)")
     ap.add_argument("--windows-per-sync", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
@@ -348,7 +348,7 @@ def main():
         raise SystemExit("bench.py: the drafter variants are built for the diffusion workloads c1-c4")
     if args.loop == "fused" and cfg.kind not in ("langevin", "phi4"):
         raise SystemExit("bench.py: --loop fused is the one-launch form of the Langevin workloads (c5, phi4)")
-    loop = args.loop or ({"c1": "graph", "c2": "multi", "c5": "fused", "phi4": "fused"}.get(cfg.name, "eager")
+    loop = args.loop or ({"c1": "graph", "c2": "multi", "c3": "multi", "c5": "fused", "phi4": "fused"}.get(cfg.name, "eager")
                          if args.drafter == "frozen" else "eager")
     elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages, args.drafter, loop,
                                                        args.windows_per_sync)
