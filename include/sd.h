@@ -55,6 +55,7 @@ typedef enum {
 } sd_status;
 
 #define SD_MAX_WINDOW 64          /* K <= 64: one wavefront ballot resolves the first rejection   */
+#define SD_STATIC_MAX_CHAINS 65536 /* largest batch sd_advance_static serves                      */
 
 #define SD_DRAFT_FROZEN 0         /* draft mean a y~ + c D0, D0 fixed over the window (Sec. 3.1)   */
 #define SD_DRAFT_EXPLICIT 1       /* caller supplies the draft means mp[B,K,d] (any drafter)       */
@@ -178,6 +179,20 @@ int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const in
 int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv,
                const uint8_t* rejected, float* y, int32_t* n, int64_t* chain_id, float* out,
                int32_t* B_active, int64_t* counters, void* stream);
+
+/* sd_advance for callers that cannot allocate device memory or hand over a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-identical results; the scratch that sd_advance keeps in the caller's
+ * workspace lives in a device array inside the library instead (16 bytes per chain, 1 MiB + 256 B
+ * per GPU, held from library load until the process ends; its address on the context's device is
+ * resolved in sd_create).  No workspace needs to be set; nothing is allocated or freed.
+ * B > SD_STATIC_MAX_CHAINS returns SD_ERR_WORKSPACE.  All contexts on one GPU share the one array
+ * and every call overwrites what the previous call left there (nothing in it has to start at
+ * zero): calls that overlap in time on one GPU -- two streams, two contexts, two host threads --
+ * race and must be ordered by the caller. */
+int sd_advance_static(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv,
+                      const uint8_t* rejected, float* y, int32_t* n, int64_t* chain_id, float* out,
+                      int32_t* B_active, int64_t* counters, void* stream);
 
 /* One speculative window of unadjusted Langevin, fused (Alg. "Speculative Sampling for
  * Unadjusted Langevin Diffusion", frozen-gradient proxy):  E(x) = -log sum_m w_m N(x; mu_m, s^2 I),

@@ -22,6 +22,7 @@ SD_DRAFT_FROZEN = 0
 SD_DRAFT_EXPLICIT = 1
 SD_DRAFT_FROZEN_REUSED = 2
 SD_MAX_WINDOW = 64
+SD_STATIC_MAX_CHAINS = 65536
 
 
 class SDError(RuntimeError):
@@ -52,6 +53,7 @@ _SIGNATURES = {
     "sdden_eval_mirror": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "sd_verify": (c_int, [c_void_p, c_int32] + [c_void_p] * 12),
     "sd_advance": (c_int, [c_void_p, c_int32] + [c_void_p] * 10),
+    "sd_advance_static": (c_int, [c_void_p, c_int32] + [c_void_p] * 10),
     "sd_langevin_window": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                    c_float, c_int32, c_float] + [c_void_p] * 6),
     "sd_langevin_window_phi4": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int32, c_float, c_float]
@@ -238,6 +240,14 @@ class Context:
             _dev(n, torch.int32, "n"), _dev(chain_id, torch.int64, "chain_id"),
             _dev(out, torch.float32, "out"), _dev(B_active, torch.int32, "B_active"),
             _dev(counters, torch.int64, "counters", True), _stream()), "sd_advance")
+
+    def sd_advance_static(self, B, y_out, adv, rejected, y, n, chain_id, out, B_active, counters=None):
+        self._check(self._lib.sd_advance_static(
+            self._h, B, _dev(y_out, torch.float32, "y_out"), _dev(adv, torch.int32, "adv"),
+            _dev(rejected, torch.uint8, "rejected", True), _dev(y, torch.float32, "y"),
+            _dev(n, torch.int32, "n"), _dev(chain_id, torch.int64, "chain_id"),
+            _dev(out, torch.float32, "out"), _dev(B_active, torch.int32, "B_active"),
+            _dev(counters, torch.int64, "counters", True), _stream()), "sd_advance_static")
 
     def sd_langevin_window(self, B, x, n, chain_id, means, logw, comp_std, M, gamma, x_out, adv,
                            rejected=None, logratio=None, logu=None):

@@ -25,6 +25,7 @@ struct sd_ctx {
   const float* start_pred = nullptr;   // EXPLICIT mode: D(y_n, n) as [B,d], replaces row 0 of Dq
   void* ws = nullptr;
   size_t ws_bytes = 0;
+  void* static_ws = nullptr;           // this device's copy of the library's static scratch (sd_advance_static)
   int device = 0;
   std::string err;
 };

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <mutex>
 #include <new>
 
 #include "sd_internal.h"
@@ -648,6 +649,35 @@ __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __res
 
 int check_ctx(sd_ctx* ctx) { return ctx ? SD_OK : SD_ERR_ARG; }
 
+// ---------------------------------------------------------------------------------------------
+// Scratch of sd_advance_static: the same layout sd_advance keeps in the caller's workspace (ids, ranks,
+// new steps, survivor totals) for up to SD_STATIC_MAX_CHAINS chains, as a device array of the library
+// itself.  Every GPU holds its own copy at its own address: sd_create resolves that address once per
+// device (with the device current) and host code only ever uses the resolved pointer.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes =
+    static_cast<size_t>(SD_STATIC_MAX_CHAINS) * 16 + (SD_STATIC_MAX_CHAINS / kScanBlock) * 4;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on `device`, which must be the current device.  Resolved on first use per device.
+hipError_t static_scratch(int device, void** out) {
+  *out = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
+
 template <int TPC, int VEC>
 void launch_verify(bool frozen, int B, hipStream_t st, const VerifyArgs& p) {
   constexpr int CPW = kBlock / TPC;
@@ -680,6 +710,7 @@ int sd_create(const sd_schedule* s, int32_t d, int32_t K, sd_ctx** out) {
   if (!ctx) return sdi::fail(g_create_error, SD_ERR_ARG, "sd_create: out of host memory");
   ctx->T = s->T; ctx->d = d; ctx->K = K;
   hipError_t e = hipGetDevice(&ctx->device);
+  if (e == hipSuccess) e = static_scratch(ctx->device, &ctx->static_ws);   // this device's copy of the static scratch
   float* dev = nullptr;
   const size_t sched_floats = (3 * static_cast<size_t>(s->T) + 15) / 16 * 16;   // counters start 64-byte aligned
   if (e == hipSuccess) e = hipMalloc(&dev, sizeof(float) * sched_floats + 64);
@@ -872,22 +903,18 @@ int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const in
   return SD_OK;
 }
 
-int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, const uint8_t* rejected,
-               float* y, int32_t* n, int64_t* chain_id, float* out, int32_t* B_active,
-               int64_t* counters, void* stream) {
-  if (int rc = check_ctx(ctx)) return rc;
-  if (B < 0 || !B_active || (B > 0 && (!y_out || !adv || !y || !n || !chain_id || !out)))
-    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_advance: bad argument");
-  if (B > 0 && (!ctx->ws || ctx->ws_bytes < sd_workspace_bytes(ctx, B)))
-    return sdi::fail(ctx->err, SD_ERR_WORKSPACE, "sd_advance: workspace of %zu bytes needed for B=%d, have %zu",
-                     sd_workspace_bytes(ctx, B), B, ctx->ws_bytes);
-  hipStream_t st = static_cast<hipStream_t>(stream);
+}  // extern "C"
+
+// Both advance entry points: `ws` holds sd_workspace_bytes(ctx, B) bytes of device scratch.
+static int advance_impl(sd_ctx* ctx, void* ws, int32_t B, const float* y_out, const int32_t* adv,
+                        const uint8_t* rejected, float* y, int32_t* n, int64_t* chain_id, float* out,
+                        int32_t* B_active, int64_t* counters, hipStream_t st) {
   if (B == 0) {
     hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, st, B_active, 0);
     SD_HIP_TRY(ctx->err, hipGetLastError());
     return SD_OK;
   }
-  int64_t* id_all = static_cast<int64_t*>(ctx->ws);
+  int64_t* id_all = static_cast<int64_t*>(ws);
   int32_t* rank = reinterpret_cast<int32_t*>(id_all + B);
   int32_t* n_new = rank + B;
   int32_t* totals = n_new + B;
@@ -914,6 +941,36 @@ int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, c
   }
   SD_HIP_TRY(ctx->err, hipGetLastError());
   return SD_OK;
+}
+
+extern "C" {
+
+int sd_advance(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, const uint8_t* rejected,
+               float* y, int32_t* n, int64_t* chain_id, float* out, int32_t* B_active,
+               int64_t* counters, void* stream) {
+  if (int rc = check_ctx(ctx)) return rc;
+  if (B < 0 || !B_active || (B > 0 && (!y_out || !adv || !y || !n || !chain_id || !out)))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_advance: bad argument");
+  if (B > 0 && (!ctx->ws || ctx->ws_bytes < sd_workspace_bytes(ctx, B)))
+    return sdi::fail(ctx->err, SD_ERR_WORKSPACE, "sd_advance: workspace of %zu bytes needed for B=%d, have %zu",
+                     sd_workspace_bytes(ctx, B), B, ctx->ws_bytes);
+  return advance_impl(ctx, ctx->ws, B, y_out, adv, rejected, y, n, chain_id, out, B_active, counters,
+                      static_cast<hipStream_t>(stream));
+}
+
+int sd_advance_static(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t* adv, const uint8_t* rejected,
+                      float* y, int32_t* n, int64_t* chain_id, float* out, int32_t* B_active,
+                      int64_t* counters, void* stream) {
+  if (int rc = check_ctx(ctx)) return rc;
+  if (B < 0 || !B_active || (B > 0 && (!y_out || !adv || !y || !n || !chain_id || !out)))
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_advance_static: bad argument");
+  if (B > SD_STATIC_MAX_CHAINS)
+    return sdi::fail(ctx->err, SD_ERR_WORKSPACE, "sd_advance_static: B=%d exceeds the %d chains the static scratch holds "
+                                                 "(use sd_advance with a workspace)", B, SD_STATIC_MAX_CHAINS);
+  if (!ctx->static_ws)
+    return sdi::fail(ctx->err, SD_ERR_HIP, "sd_advance_static: the static scratch was not resolved at sd_create");
+  return advance_impl(ctx, ctx->static_ws, B, y_out, adv, rejected, y, n, chain_id, out, B_active, counters,
+                      static_cast<hipStream_t>(stream));
 }
 
 const char* sd_last_error(const sd_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
