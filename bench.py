@@ -62,9 +62,9 @@ def roofline_plan(cfg):
         H = cfg.params.H
         # the batched evaluation of the drafted states (rows = sum Kt - chain-windows); the window-start
         # call (one row per chain, a smaller tile) is left out of this figure
-        return dict(kernel="mlpgemm::kernel_hs<EPI=1,GATHER> (256x256x64 tiles, 8 waves) layer-1 GEMM of the batched target call, rows x 12288 -> 4096, "
-                           "bf16 MFMA, A rows gathered from the bf16 image of the drafts (largest share of the kernel time; layer 3 has the "
-                           "same flops and runs within 5% of it)",
+        return dict(kernel="mlpgemm::kernel_pp<EPI=1,GATHER> (256x256x64 tiles, 8 waves in two alternating groups, 16x16x32 bf16 MFMA) "
+                           "layer-1 GEMM of the batched target call, rows x 12288 -> 4096, A rows gathered from the bf16 image "
+                           "of the drafts (largest share of the kernel time; layer 3 has the same flops)",
                     den_which=1, den_min_rows=cfg.B + 1, bound="mfma", peak="mfma_bf16", scale=1e-12,
                     work=lambda c: 2.0 * (c[4] - c[1]) * d * H)
     if cfg.kind == "lowrank":
@@ -305,6 +305,53 @@ def cpu_baseline(cfg, budget_s=15.0, drafter="frozen"):
                       f"({steps_done} verified steps in {dt:.1f} s; numpy fp64)"}
 
 
+def kernel_gemm(iters=20, rows_per_chain_masked=1, variants=None):
+    """The three GEMMs of the c4 batched target call in isolation, back to back on fixed data: rows = the
+    B*(K-1) drafted states a full window evaluates (the last draft of every chain is masked, as in the sampler),
+    bf16 image supplied, each layer timed with HIP events on the launch stream by the library's profiling
+    hooks.  One JSON line per kernel variant (sdden_mlp_select_gemm)."""
+    import torch
+    import workloads as W
+    from paper_2501_05370_amd.runner import make_denoiser
+    torch.cuda.set_device(0)
+    cfg = W.make_config("c4")
+    B, K, d, H = cfg.B, cfg.K, cfg.d, cfg.params.H
+    R = B * K
+    den = make_denoiser(cfg, R)
+    g = torch.Generator(device="cuda").manual_seed(0)
+    X = torch.randn(R, d, device="cuda", generator=g)
+    Xb = X.to(torch.bfloat16).view(torch.int16).contiguous()
+    krow = torch.randint(0, cfg.T, (B, K), device="cuda", generator=g, dtype=torch.int32)
+    krow[:, K - rows_per_chain_masked:] = -1
+    rows = int((krow >= 0).sum().item())
+    out = torch.zeros(R + 1, d, device="cuda")
+    flops = {1: 2.0 * rows * d * H, 2: 2.0 * rows * H * H, 3: 2.0 * rows * H * d}
+    ref = None
+    names = {0: "kernel_pp", 1: "kernel_hs", 2: "kernel_pp without fragment reads (timing only)",
+             3: "kernel_pp without direct loads (timing only)", 4: "kernel_pp, MFMAs and barriers only (timing only)"}
+    vs = [(v, names[v]) for v in (variants or [0, 1, 2, 3, 4])]
+    for variant, name in vs:
+        den.sdden_mlp_select_gemm(variant)
+        for _ in range(2):
+            den.sdden_eval_mirror(R, X, Xb, krow.view(-1), out[1:])
+        torch.cuda.synchronize()
+        if ref is None:
+            ref = out.clone()
+        layers = {"max_abs_diff_vs_first_variant": float((out - ref).abs().max().item())}
+        for which in (1, 2, 3):
+            den.sdden_profile(which)
+            for _ in range(iters):
+                den.sdden_eval_mirror(R, X, Xb, krow.view(-1), out[1:])
+            ms, n = den.sdden_profile_collect()
+            den.sdden_profile(0)
+            us = 1e3 * ms / max(1, n)
+            layers[f"layer{which}"] = {"avg_launch_us": round(us, 2), "launches": n,
+                                       "PFLOP/s": round(flops[which] / (us * 1e-6) * 1e-15, 4),
+                                       "frac_of_2.5": round(flops[which] / (us * 1e-6) * 1e-15 / 2.5, 4)}
+        print(json.dumps({"kernel": "mlp_gemm", "variant": name, "rows": rows, "d": d, "H": H,
+                          "note": "back-to-back launches of the three layers on fixed data", **layers}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -326,6 +373,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the untimed extras (acceptance by position, sequential chain on the GPU)")
+    ap.add_argument("--kernel", default=None, choices=["gemm"],
+                    help="time one kernel family in isolation instead of the sampler (controlled runs behind the "
+                         "bounds quoted for the kernels): gemm = the three MLP GEMMs of the c4 batched call")
+    ap.add_argument("--variants", default=None, help="with --kernel gemm: comma-separated sdden_mlp_select_gemm codes")
+    ap.add_argument("--iters", type=int, default=20, help="launches per timed kernel with --kernel")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprof FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -337,6 +389,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 5}))
+        return
+    if args.kernel == "gemm":
+        kernel_gemm(args.iters, variants=[int(v) for v in args.variants.split(",")] if args.variants else None)
         return
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (chains are independent and would shard by "

@@ -80,6 +80,13 @@ int sdden_profile(sdden* den, int32_t which);
 int sdden_profile_min_rows(sdden* den, int32_t min_rows);
 int sdden_profile_collect(sdden* den, double* total_ms, int64_t* launches);
 
+/* Measurement aid (mlp only): which kernel serves the 256 x 256 GEMM tile of the batched call.
+ * 0 = the default (alternating-phase kernel); 1 = the earlier hand-scheduled kernel, kept so that
+ * the two can be timed side by side on the same data (results agree).  2, 3, 4 = the default
+ * kernel with its fragment reads / its direct loads / both left out: TIMING ONLY, the results are
+ * wrong -- they locate what bounds the kernel (4 = the MFMA and barrier schedule alone). */
+int sdden_mlp_select_gemm(sdden* den, int32_t variant);
+
 int sdden_destroy(sdden* den);
 const char* sdden_last_error(const sdden* den);
 

@@ -76,6 +76,7 @@ _SIGNATURES = {
     "sdden_profile": (c_int, [c_void_p, c_int32]),
     "sdden_profile_min_rows": (c_int, [c_void_p, c_int32]),
     "sdden_profile_collect": (c_int, [c_void_p, POINTER(ctypes.c_double), POINTER(c_int64)]),
+    "sdden_mlp_select_gemm": (c_int, [c_void_p, c_int32]),
     "sdden_destroy": (c_int, [c_void_p]),
     "sdden_last_error": (c_char_p, [c_void_p]),
 }
@@ -366,6 +367,9 @@ class Denoiser:
         self._check(self._lib.sdden_profile_collect(self._h, ctypes.byref(ms), ctypes.byref(n)),
                     "sdden_profile_collect")
         return ms.value, n.value
+
+    def sdden_mlp_select_gemm(self, variant: int):
+        self._check(self._lib.sdden_mlp_select_gemm(self._h, variant), "sdden_mlp_select_gemm")
 
     def sdden_set_active_count(self, count: Optional[torch.Tensor], rows_per_chain: int = 1):
         self._keep_count = count

@@ -219,17 +219,21 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
   }
 }
 
+// Raises the kernel's dynamic-LDS limit on the current device.  Done for every instantiation when a denoiser is
+// created, never on the launch path: the launch sequence is then free of one-time set-up calls (a HIP graph can
+// capture its very first use) and of unsynchronised "already done" flags.
+template <int BM, int BN, int WM, int WN, int EPI, int NS, bool GATHER = false, int PM = 4, int PN = 8>
+hipError_t prepare() {
+  constexpr size_t shmem = NS * static_cast<size_t>(BM + BN) * 128;
+  static_assert(NS >= 2 && shmem <= 160 * 1024, "ring must fit the 160 KiB of LDS");
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, EPI, NS, GATHER, PM, PN>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
+}
+
+// prepare<...>() must have run for the instantiation on this device.
 template <int BM, int BN, int WM, int WN, int EPI, int NS, bool GATHER = false, int PM = 4, int PN = 8>
 hipError_t launch(const Args& a, int Rmax, hipStream_t st) {
   constexpr size_t shmem = NS * static_cast<size_t>(BM + BN) * 128;
-  static_assert(NS >= 2 && shmem <= 160 * 1024, "ring must fit the 160 KiB of LDS");
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, EPI, NS, GATHER, PM, PN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   const int tiles_m = (Rmax + BM - 1) / BM, tiles_n = a.N / BN;
   const int patches = ((tiles_m + PM - 1) / PM) * ((tiles_n + PN - 1) / PN);
   const int grid = (patches * PM * PN + 7) / 8 * 8;
@@ -422,15 +426,14 @@ __global__ __launch_bounds__(512) void kernel_hs(Args p) {
 inline bool hs_applicable(const Args& a) { return a.Kdim >= 128 && (a.Kdim / BK) % 2 == 0; }
 
 template <int EPI, bool GATHER = false, int PM = 4, int PN = 8>
+hipError_t prepare_hs() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel_hs<EPI, GATHER, PM, PN>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
+}
+
+template <int EPI, bool GATHER = false, int PM = 4, int PN = 8>
 hipError_t launch_hs(const Args& a, int Rmax, hipStream_t st) {
   constexpr size_t shmem = 131072;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel_hs<EPI, GATHER, PM, PN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   const int tiles_m = (Rmax + 255) / 256, tiles_n = a.N / 256;
   const int patches = ((tiles_m + PM - 1) / PM) * ((tiles_n + PN - 1) / PN);
   const int grid = (patches * PM * PN + 7) / 8 * 8;

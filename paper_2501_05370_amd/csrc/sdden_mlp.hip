@@ -21,6 +21,7 @@
 #include <vector>
 
 #include "mlp_gemm.h"
+#include "mlp_gemm_pp.h"
 #include "sdden_internal.h"
 #include "sdden_rows.h"
 
@@ -58,6 +59,21 @@ float bf16_bits_to_float(uint16_t b) {
   return f;
 }
 
+// Dynamic-LDS limits of every GEMM instantiation launch_gemm can pick, on the current device.
+template <int EPI, bool GATHER>
+hipError_t prepare_gemms() {
+  hipError_t e = mlpgemm::prepare<256, 256, 2, 4, EPI, 2, GATHER>();
+  if (e == hipSuccess) e = mlpgemm::prepare<128, 128, 2, 2, EPI, 2, GATHER>();
+  if (e == hipSuccess) e = mlpgemm::prepare<64, 128, 2, 2, EPI, 2, GATHER>();
+  if (e == hipSuccess) e = mlpgemm::prepare<64, 128, 2, 2, EPI, 4, GATHER>();
+  if (e == hipSuccess) e = mlpgemm::prepare_hs<EPI, GATHER>();
+  if (e == hipSuccess) e = mlpgemm::prepare_pp<EPI, GATHER>();
+  if (e == hipSuccess) e = mlpgemm::prepare_pp<EPI, GATHER, 1>();
+  if (e == hipSuccess) e = mlpgemm::prepare_pp<EPI, GATHER, 2>();
+  if (e == hipSuccess) e = mlpgemm::prepare_pp<EPI, GATHER, 3>();
+  return e;
+}
+
 // Tile choice by how well the launch fills the 256 CUs.  The 256x256 tile (8 wavefronts, two LDS
 // stages) has the highest rate per CU and is taken when its rounds of workgroups are at least 60 % full
 // over the whole launch (at 71 % -- 544 tiles in three rounds -- it still runs the call 5 % faster than
@@ -65,13 +81,19 @@ float bf16_bits_to_float(uint16_t b) {
 // that gives 512 tiles or more, else 64x128: with at most one workgroup per CU (the window-start
 // call) as a four-stage ring, with more as two stages so that three workgroups share a CU.
 template <int EPI, bool GATHER = false>
-int launch_gemm(const mlpgemm::Args& a, int R, hipStream_t st, std::string& err) {
+int launch_gemm(const mlpgemm::Args& a, int R, hipStream_t st, std::string& err, int variant) {
   const int t256 = ((R + 255) / 256) * (a.N / 256);
   const int t128 = ((R + 127) / 128) * (a.N / 128);
   const int t64 = ((R + 63) / 64) * (a.N / 128);
   hipError_t e;
-  if (10 * t256 >= 6 * ((t256 + 255) / 256) * 256)
-    e = mlpgemm::hs_applicable(a) ? mlpgemm::launch_hs<EPI, GATHER>(a, R, st) : mlpgemm::launch<256, 256, 2, 4, EPI, 2, GATHER>(a, R, st);
+  if (10 * t256 >= 6 * ((t256 + 255) / 256) * 256) {
+    if (!mlpgemm::hs_applicable(a)) e = mlpgemm::launch<256, 256, 2, 4, EPI, 2, GATHER>(a, R, st);
+    else if (variant == 1) e = mlpgemm::launch_hs<EPI, GATHER>(a, R, st);
+    else if (variant == 2) e = mlpgemm::launch_pp<EPI, GATHER, 1>(a, R, st);
+    else if (variant == 3) e = mlpgemm::launch_pp<EPI, GATHER, 2>(a, R, st);
+    else if (variant == 4) e = mlpgemm::launch_pp<EPI, GATHER, 3>(a, R, st);
+    else e = mlpgemm::launch_pp<EPI, GATHER>(a, R, st);
+  }
   else if (t128 >= 512) e = mlpgemm::launch<128, 128, 2, 2, EPI, 2, GATHER>(a, R, st);
   else if (t64 > 256) e = mlpgemm::launch<64, 128, 2, 2, EPI, 2, GATHER>(a, R, st);
   else e = mlpgemm::launch<64, 128, 2, 2, EPI, 4, GATHER>(a, R, st);
@@ -86,6 +108,7 @@ struct MlpDenoiser final : sdden {
   int32_t *rowidx = nullptr, *count = nullptr;
   uint16_t *Xb = nullptr, *H1 = nullptr, *H2 = nullptr;
   int cap_rows = 0;
+  int gemm_variant = 0;          // 0: kernel_pp; measurement only: 1 = kernel_hs, 2..4 = kernel_pp with pieces left out
 
   ~MlpDenoiser() override {
     for (void* q : {static_cast<void*>(W1t), static_cast<void*>(W2t), static_cast<void*>(W3t), static_cast<void*>(tb),
@@ -124,7 +147,10 @@ struct MlpDenoiser final : sdden {
   int eval_impl(int R, const float* X, const uint16_t* Xbf16, const int32_t* krow, float* out, hipStream_t st) {
     if (R > cap_rows)
       return sdi::fail(err, SD_ERR_WORKSPACE, "sdden_eval(mlp): %d rows exceed the %d reserved (sdden_reserve)", R, cap_rows);
-    if (!sdi::aligned16(X)) return sdi::fail(err, SD_ERR_ARG, "sdden_eval(mlp): X must be 16-byte aligned");
+    if (!sdi::aligned16(X) || !sdi::aligned16(out))
+      return sdi::fail(err, SD_ERR_ARG, "sdden_eval(mlp): X and out must be 16-byte aligned");
+    if (Xbf16 && !sdi::aligned16(Xbf16))
+      return sdi::fail(err, SD_ERR_ARG, "sdden_eval_mirror(mlp): Xbf16 must be 16-byte aligned");
     hipLaunchKernelGGL(sdrows::compact_rows_kernel, dim3(1), dim3(sdrows::kScan), 0, st, krow, rowidx, count,
                        active, rows_per_chain, R);
     mlpgemm::Args a;
@@ -132,10 +158,9 @@ struct MlpDenoiser final : sdden {
     int rc;
     a.Bt = W1t; a.N = H; a.Kdim = d; a.bias = tb; a.outb = H1; a.outf = nullptr;
     if (Xbf16) {
-      if (!sdi::aligned16(Xbf16)) return sdi::fail(err, SD_ERR_ARG, "sdden_eval_mirror(mlp): Xbf16 must be 16-byte aligned");
       a.A = Xbf16; a.arow = rowidx;
       prof.mark(1, st);
-      rc = launch_gemm<1, true>(a, R, st, err);
+      rc = launch_gemm<1, true>(a, R, st, err, gemm_variant);
       prof.mark(1, st);
     } else {
       const int64_t chunks = static_cast<int64_t>(R) * (d / 8);
@@ -143,19 +168,19 @@ struct MlpDenoiser final : sdden {
       hipLaunchKernelGGL(gather_convert_kernel, dim3(cgrid), dim3(kThreads), 0, st, X, rowidx, count, Xb, d);
       a.A = Xb;
       prof.mark(1, st);
-      rc = launch_gemm<1>(a, R, st, err);
+      rc = launch_gemm<1>(a, R, st, err, gemm_variant);
       prof.mark(1, st);
     }
     a.arow = nullptr;
     if (rc) return rc;
     a.A = H1; a.Bt = W2t; a.N = H; a.Kdim = H; a.bias = b2; a.outb = H2;
     prof.mark(2, st);
-    rc = launch_gemm<2>(a, R, st, err);
+    rc = launch_gemm<2>(a, R, st, err, gemm_variant);
     prof.mark(2, st);
     if (rc) return rc;
     a.A = H2; a.Bt = W3t; a.N = d; a.Kdim = H; a.bias = b3; a.outb = nullptr; a.outf = out;
     prof.mark(3, st);
-    rc = launch_gemm<3>(a, R, st, err);
+    rc = launch_gemm<3>(a, R, st, err, gemm_variant);
     prof.mark(3, st);
     if (rc) return rc;
     SD_HIP_TRY(err, hipGetLastError());
@@ -211,7 +236,10 @@ extern "C" int sdden_mlp_create(int32_t d, int32_t H, int32_t E, const uint16_t*
   transpose_bits(W1, d, H, w1t);      // first d rows of W1 only: [d,H] -> [H,d]
   transpose_bits(W2, H, H, w2t);
   transpose_bits(W3, H, d, w3t);      // [H,d] -> [d,H]
-  hipError_t e = hipSuccess;
+  hipError_t e = prepare_gemms<1, false>();
+  if (e == hipSuccess) e = prepare_gemms<1, true>();
+  if (e == hipSuccess) e = prepare_gemms<2, false>();
+  if (e == hipSuccess) e = prepare_gemms<3, false>();
   auto up = [&](auto** dst, const void* src, size_t bytes) {
     if (e != hipSuccess) return;
     e = hipMalloc(reinterpret_cast<void**>(dst), bytes);
@@ -233,5 +261,14 @@ extern "C" int sdden_mlp_create(int32_t d, int32_t H, int32_t E, const uint16_t*
     return rc;
   }
   *out = m;
+  return SD_OK;
+}
+
+// Measurement aid: which kernel serves the 256 x 256 tile (0 = default, 1 = kernel_hs).
+extern "C" int sdden_mlp_select_gemm(sdden* den, int32_t variant) {
+  MlpDenoiser* m = dynamic_cast<MlpDenoiser*>(den);
+  if (!m) return SD_ERR_ARG;
+  if (variant < 0 || variant > 4) return sdi::fail(m->err, SD_ERR_ARG, "sdden_mlp_select_gemm: variant must be 0..4");
+  m->gemm_variant = variant;
   return SD_OK;
 }
