@@ -109,7 +109,7 @@ def _sampler(cfg, drafter):
     return make_sampler(cfg, drafter=drafter)
 
 
-def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1):
+def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1, verify_shape=0):
     import torch
     from paper_2501_05370_amd.runner import make_sampler
     from paper_2501_05370_amd.sampler import StageTimer
@@ -118,6 +118,8 @@ def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1):
         raise SystemExit("bench.py needs a GPU (the HIP library has no CPU fallback)")
     torch.cuda.set_device(0)
     smp = _sampler(cfg, drafter)
+    if verify_shape:
+        smp.ctx.sd_set_verify_shape(verify_shape)
     ids = torch.arange(cfg.B, dtype=torch.int64, device="cuda")
     plan = roofline_plan(cfg)
     run_kw = {} if loop in ("eager", "fused") else dict(windows_per_sync=wps, graph=(loop == "graph"))
@@ -352,6 +354,144 @@ def kernel_gemm(iters=20, rows_per_chain_masked=1, variants=None):
                           "note": "back-to-back launches of the three layers on fixed data", **layers}), flush=True)
 
 
+def kernel_verify(workload, accept, shapes, iters=20):
+    """The accept / first-reject / reflect kernel alone, at the batch size of a workload, on inputs whose first
+    rejection is planted: `all` = every draft accepted (prediction rows equal the window-start prediction, so
+    Delta = 0), `second` = every chain rejects its second draft, `mixed` = the first rejection of a chain is
+    geometric with per-position acceptance 0.55 (the shape the c4 sampler shows after its first windows).  Reports,
+    per launch shape, the mean launch time and the rate of the bytes the method needs (rows up to the first
+    rejection, the four rows of the reflection, the state written) and of the rows the group schedule streams."""
+    import torch
+    import workloads as W
+    from paper_2501_05370_amd.runner import make_context
+    torch.cuda.set_device(0)
+    cfg = W.make_config(workload)
+    B, K, d, T = cfg.B, cfg.K, cfg.d, cfg.T
+    ctx = make_context(cfg)
+    g = torch.Generator(device="cuda").manual_seed(0)
+    y = torch.randn(B, d, device="cuda", generator=g)
+    D0 = torch.randn(B, d, device="cuda", generator=g)
+    Ytil = torch.randn(B, K, d, device="cuda", generator=g)
+    Dq = D0[:, None, :].repeat(1, K, 1).contiguous()                  # Delta = 0 everywhere: accepted
+    n = torch.full((B,), T // 2, dtype=torch.int32, device="cuda")
+    ids = torch.arange(B, dtype=torch.int64, device="cuda")
+    if accept == "all":
+        jr = torch.full((B,), K, dtype=torch.int64)                    # K = no rejection
+    elif accept == "second":
+        jr = torch.ones(B, dtype=torch.int64)
+    else:
+        rng = np.random.default_rng(0)
+        jr = torch.as_tensor(np.minimum(K, 1 + rng.geometric(0.45, size=B) - 1 + 0), dtype=torch.int64)
+        jr = torch.clamp(jr, min=1)                                    # the first draft of a frozen window is exact
+    rows = torch.arange(B)
+    rej = jr < K
+    Dq[rows[rej], jr[rej]] += 1.0e3                                    # a draft mean this far off is rejected
+    y_out = torch.zeros(B, d, device="cuda")
+    adv = torch.zeros(B, dtype=torch.int32, device="cuda")
+    rejected = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    row = 4.0 * d
+    jrn = jr.numpy().astype(np.float64)
+    # rows the method needs: y, D0, drafts 0..jr, predictions 1..jr; then the reflection re-reads three and
+    # writes one (a fully accepted window copies its last draft: one read, one write)
+    need = np.where(jrn < K, (2 * jrn + 3) + 4, (2 * K + 1) + 2).sum() * row
+    for shape in shapes:
+        ctx.sd_set_verify_shape(shape)
+        for _ in range(3):
+            ctx.sd_verify(B, y, n, ids, D0, Dq, Ytil, y_out, adv, rejected)
+        torch.cuda.synchronize()
+        got = adv.cpu().numpy()
+        assert np.array_equal(got, np.where(jrn < K, jrn + 1, K).astype(np.int32)), "planted first rejections not found"
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            ctx.sd_verify(B, y, n, ids, D0, Dq, Ytil, y_out, adv, rejected)
+        e1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / iters
+        print(json.dumps({"kernel": "verify_kernel", "workload": workload, "accept": accept, "shape": shape,
+                          "chains": B, "d": d, "K": K, "mean_advance": float(np.where(jrn < K, jrn + 1, K).mean()),
+                          "avg_launch_us": round(us, 2), "needed_bytes_per_launch": need,
+                          "needed_TB/s": round(need / (us * 1e-6) * 1e-12, 3),
+                          "frac_of_8_TB/s": round(need / (us * 1e-6) * 1e-12 / 8.0, 4),
+                          "note": "back-to-back launches on fixed data (event bracket over all launches)"}), flush=True)
+
+
+def _time_launches(fn, iters, warm=3):
+    """Mean duration in microseconds of `iters` back-to-back calls of fn (events on the launch stream)."""
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return 1e3 * e0.elapsed_time(e1) / iters
+
+
+def kernel_stream(iters=20):
+    """What a plain hand-written streaming kernel reaches on this chip (sd_measure_stream): copy, read and fill
+    of buffers the size of the c4 window arrays (403 MB) and of 1 GiB."""
+    import torch
+    from paper_2501_05370_amd import binding
+    torch.cuda.set_device(0)
+    for nbytes in (512 * 16 * 12288 * 4, 1 << 30):
+        src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for mode, name, moved in ((0, "copy", 2 * nbytes), (1, "read", nbytes), (2, "fill", nbytes)):
+            us = _time_launches(lambda: binding.sd_measure_stream(src, dst, nbytes, mode), iters)
+            print(json.dumps({"kernel": "stream_kernel", "mode": name, "buffer_bytes": nbytes, "bytes_moved": moved,
+                              "avg_launch_us": round(us, 2), "TB/s": round(moved / (us * 1e-6) * 1e-12, 3),
+                              "frac_of_8_TB/s": round(moved / (us * 1e-6) * 1e-12 / 8.0, 4)}), flush=True)
+        del src, dst
+
+
+def kernel_mfma(iters=20):
+    """What a loop of nothing but MFMAs on register operands sustains (sd_measure_mfma): the matrix cores under
+    the chip's power management, with no operand traffic at all."""
+    import torch
+    from paper_2501_05370_amd import binding
+    torch.cuda.set_device(0)
+    sink = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    for shape, name in ((0, "v_mfma_f32_32x32x16_bf16"), (1, "v_mfma_f32_16x16x32_bf16")):
+        rounds = 20000
+        flops = binding.sd_measure_mfma(shape, rounds, sink)
+        us = _time_launches(lambda: binding.sd_measure_mfma(shape, rounds, sink), iters)
+        print(json.dumps({"kernel": "mfma_kernel", "instruction": name, "workgroups": "one of 512 threads per CU",
+                          "rounds_of_16_mfma": rounds, "avg_launch_us": round(us, 2),
+                          "PFLOP/s": round(flops / (us * 1e-6) * 1e-15, 4),
+                          "frac_of_2.5": round(flops / (us * 1e-6) * 1e-15 / 2.5, 4)}), flush=True)
+
+
+def kernel_draft(workload, iters=20):
+    """The frozen draft rollout alone at the batch size of a workload (all chains mid-run, full windows): bytes
+    written per launch (fp32 drafts, plus their bf16 image where the target network reads bf16) over its time."""
+    import torch
+    import workloads as W
+    from paper_2501_05370_amd.runner import make_context
+    torch.cuda.set_device(0)
+    cfg = W.make_config(workload)
+    B, K, d, T = cfg.B, cfg.K, cfg.d, cfg.T
+    ctx = make_context(cfg)
+    g = torch.Generator(device="cuda").manual_seed(0)
+    y = torch.randn(B, d, device="cuda", generator=g)
+    D0 = torch.randn(B, d, device="cuda", generator=g)
+    n = torch.full((B,), T // 2, dtype=torch.int32, device="cuda")
+    ids = torch.arange(B, dtype=torch.int64, device="cuda")
+    Ytil = torch.zeros(B, K, d, device="cuda")
+    krow = torch.zeros(B, K, dtype=torch.int32, device="cuda")
+    mirror = torch.zeros(B, K, d, dtype=torch.int16, device="cuda") if cfg.kind == "mlp" else None
+    ctx.sd_set_draft_mirror(mirror)
+    us = _time_launches(lambda: ctx.sd_draft(B, y, n, ids, D0, Ytil, krow), iters)
+    moved = B * K * d * (4 + (2 if mirror is not None else 0)) + 2 * B * d * 4
+    print(json.dumps({"kernel": "draft_frozen_kernel", "workload": workload, "chains": B, "d": d, "K": K,
+                      "bf16_image": mirror is not None, "bytes_moved": moved, "avg_launch_us": round(us, 2),
+                      "TB/s": round(moved / (us * 1e-6) * 1e-12, 3),
+                      "normals_per_second": round(B * K * d / (us * 1e-6), 1)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -370,12 +510,18 @@ def main():
                          "(sd_langevin_run: bit-identical results, no compaction needed).  Default: graph for c1, multi for "
                          "c2 and c3, fused for c5 and phi4 (whichever measured faster), eager for c4 (windows of 2 ms: no difference)")
     ap.add_argument("--windows-per-sync", type=int, default=4)
+    ap.add_argument("--verify-shape", type=int, default=0,
+                    help="launch shape of the accept / reflect kernel in the sampler (sd_set_verify_shape; 0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the untimed extras (acceptance by position, sequential chain on the GPU)")
-    ap.add_argument("--kernel", default=None, choices=["gemm"],
+    ap.add_argument("--accept", default="mixed", choices=["all", "second", "mixed"], help="with --kernel verify")
+    ap.add_argument("--shapes", default="0", help="with --kernel verify: comma-separated sd_set_verify_shape codes")
+    ap.add_argument("--kernel", default=None, choices=["gemm", "verify", "draft", "stream", "mfma"],
                     help="time one kernel family in isolation instead of the sampler (controlled runs behind the "
-                         "bounds quoted for the kernels): gemm = the three MLP GEMMs of the c4 batched call")
+                         "bounds quoted for the kernels): gemm = the three MLP GEMMs of the c4 batched call; verify = the "
+                         "accept / reflect kernel on planted rejections (--workload, --accept, --shapes); draft = the frozen "
+                         "rollout; stream / mfma = the plain copy and MFMA-only kernels the bounds are compared with")
     ap.add_argument("--variants", default=None, help="with --kernel gemm: comma-separated sdden_mlp_select_gemm codes")
     ap.add_argument("--iters", type=int, default=20, help="launches per timed kernel with --kernel")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -393,6 +539,18 @@ def main():
     if args.kernel == "gemm":
         kernel_gemm(args.iters, variants=[int(v) for v in args.variants.split(",")] if args.variants else None)
         return
+    if args.kernel == "stream":
+        kernel_stream(args.iters)
+        return
+    if args.kernel == "mfma":
+        kernel_mfma(args.iters)
+        return
+    if args.kernel == "draft":
+        kernel_draft(args.workload, args.iters)
+        return
+    if args.kernel == "verify":
+        kernel_verify(args.workload, args.accept, [int(v) for v in args.shapes.split(",")], args.iters)
+        return
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (chains are independent and would shard by "
                          "chain id with no collective on the hot path); run with --gpus 1")
@@ -406,7 +564,7 @@ def main():
     loop = args.loop or ({"c1": "graph", "c2": "multi", "c3": "multi", "c5": "fused", "phi4": "fused"}.get(cfg.name, "eager")
                          if args.drafter == "frozen" else "eager")
     elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages, args.drafter, loop,
-                                                       args.windows_per_sync)
+                                                       args.windows_per_sync, args.verify_shape)
     total_steps = counters[0]
     assert total_steps == cfg.B * cfg.T * steps, (total_steps, cfg.B, cfg.T, steps)
     line = {

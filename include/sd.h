@@ -98,6 +98,11 @@ int sd_set_draft_mode(sd_ctx* ctx, int mode);           /* SD_DRAFT_FROZEN (defa
 int sd_set_carry(sd_ctx* ctx, const float* Dq_ext, float* D_frozen);
 /* Temperature tau > 0 of the accept test (App. "Influence of the temperature"); 1 = exact.       */
 int sd_set_temperature(sd_ctx* ctx, float tau);
+/* Measurement aid: launch shape of the accept / reflect kernel for rows of more than 256 16-byte
+ * columns, as (threads per chain, window positions per group): 1 = (256,4); 2 = (256,2);
+ * 3 = (512,4); 4 = (512,2); 0 = the default for the row length (2 up to 1024 columns, 4 above).
+ * Results are bit-identical among the shapes with the same number of threads. */
+int sd_set_verify_shape(sd_ctx* ctx, int32_t shape);
 /* Optional device-resident batch size.  When set (non-NULL, dev int32), every window call treats
  * only the first min(B, *count) chains as present, so a fixed launch sequence (for instance a
  * captured HIP graph) keeps working while sd_advance shrinks the batch.  NULL restores B.        */
@@ -202,9 +207,9 @@ int sd_advance_static(sd_ctx* ctx, int32_t B, const float* y_out, const int32_t*
  * in : x [B,d], n [B], chain_id [B]; means [M,d]; logw [M] (log weights); comp_std = s; gamma (dev)
  * out: x_out [B,d], adv [B], rejected [B] or NULL; logratio, logu [B,K] or NULL as in sd_verify.
  * Calls on one context must be ordered (one stream, or events between streams): for d <= 1024 the
- * kernel hands chains to its wavefronts through two counters that belong to the context, which the
- * last wavefront of a launch rewinds; two launches of one context in flight at once would share
- * them.  Different contexts are independent. */
+ * kernel hands chains to its wavefronts through a counter that belongs to the context, zeroed by a
+ * one-thread kernel ahead of every launch; two launches of one context in flight at once would
+ * share it.  Different contexts are independent. */
 int sd_langevin_window(sd_ctx* ctx, int32_t B, const float* x, const int32_t* n,
                        const int64_t* chain_id, const float* means, const float* logw,
                        float comp_std, int32_t M, float gamma, float* x_out, int32_t* adv,

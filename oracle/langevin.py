@@ -1,16 +1,21 @@
 """ORACLE (test infrastructure only) -- speculative sampling for unadjusted Langevin, in fp64.
 
-Follows Alg. "Speculative Sampling for Unadjusted Langevin Diffusion" (App. on Langevin
-diffusions) step by step, vectorised over independent chains only:
+What it computes (Sec. 5 and the Langevin appendix, Alg. "Speculative Sampling for Unadjusted
+Langevin Diffusion"), vectorised over independent chains only.  The target chain is unadjusted
+Langevin on an energy E: a gradient step of size gamma plus Gaussian noise of variance 2 gamma.
+The draft chain is the same step with a cheaper gradient in place of grad E -- a proxy energy's, or
+the gradient at the window's first state kept for the whole window (the frozen drafter).  A window
+drafts up to K states one after the other, evaluates grad E at all of them at once, and then walks
+them in order: each drafted state is tested with the reflection-coupling rule for two Gaussians of
+equal covariance whose means differ by sqrt(2 gamma) * Delta, Delta being sqrt(gamma/2) times the
+gap between the true and the proxy gradient at the previous state, with Z the noise that drew the
+draft; the first rejected draft is replaced by the target step from the previous state driven by
+Z reflected across Delta, and the window ends there.  The optional temperature divides the log
+acceptance ratio (App. "Influence of the temperature"); 1 is the exact sampler.
 
-    target   X_{k+1} = X_k - gamma grad E(X_k)     + sqrt(2 gamma) W_k
-    draft    X_{k+1} = X_k - gamma grad E^(X_k)    + sqrt(2 gamma) W_k
-    Delta_{k-1} = sqrt(gamma/2) (grad E(Y~_{k-1}) - grad E^(Y~_{k-1})),  e = Delta/|Delta|
-    accept iff U <= min(1, N(Z + Delta; 0, I) / N(Z; 0, I)),  Z = the noise that drew Y~_k
-    on reject  Y_k = Y~_{k-1} - gamma grad E(Y~_{k-1}) + sqrt(2 gamma) (I - 2 e e^T) Z
-
-(the listing's reject branch prints "gamma E": read as gamma grad E, as in the target update).
-The proxy is either a cheaper gradient or the frozen one, grad E^(x_{n+j}) = grad E(x_n).
+Readings: the reject branch of the appendix's algorithm prints the energy where the target step
+needs its gradient (taken as the gradient, as in the target update); the start state is drawn
+N(0, Id) from the keyed initial stream (the paper leaves it arbitrary).
 
 This is written independently of oracle/speculative.py on purpose: the two formulations are
 pinned to each other in tests/test_oracle_langevin.py (the ULA chain is the general Gaussian
@@ -60,9 +65,10 @@ class Phi4Energy:
 
 
 def ula_window(gradE: Grad, x, n, chain_id, K: int, T: int, gamma: float, seed: int,
-               grad_proxy: Optional[Grad] = None):
+               grad_proxy: Optional[Grad] = None, tau: float = 1.0):
     """One window for every chain.  Returns (x_out [B,d], adv [B], rejected [B],
-    logratio [B,K], logu [B,K]).  ``grad_proxy`` None = frozen gradient."""
+    logratio [B,K], logu [B,K]).  ``grad_proxy`` None = frozen gradient; ``tau`` = temperature of
+    the accept test (the reported log-ratios are already divided by it)."""
     x = np.asarray(x, dtype=np.float64)
     n = np.asarray(n)
     B, d = x.shape
@@ -105,7 +111,7 @@ def ula_window(gradE: Grad, x, n, chain_id, K: int, T: int, gamma: float, seed: 
         z = Z[act, j - 1]
         zd = np.sum(z * Delta, axis=1)
         dd = np.sum(Delta * Delta, axis=1)
-        lr = -zd - 0.5 * dd                                   # log N(Z+Delta) - log N(Z)
+        lr = (-zd - 0.5 * dd) / tau                           # (log N(Z+Delta) - log N(Z)) / tau
         lu = np.log(philox.uniforms(seed, chain_id[act], n[act] + j))
         acc = (dd == 0.0) | (lu <= np.minimum(0.0, lr))
         with np.errstate(divide="ignore", invalid="ignore"):
@@ -126,8 +132,8 @@ def ula_window(gradE: Grad, x, n, chain_id, K: int, T: int, gamma: float, seed: 
 
 
 def ula_sample(gradE: Grad, B: int, d: int, K: int, T: int, gamma: float, seed: int,
-               grad_proxy: Optional[Grad] = None, chain_ids: Optional[np.ndarray] = None):
-    """Whole algorithm; X_0 ~ N(0, Id) from the keyed initial stream ("Set Y_0 arbitrarily").
+               grad_proxy: Optional[Grad] = None, chain_ids: Optional[np.ndarray] = None, tau: float = 1.0):
+    """Whole algorithm; X_0 ~ N(0, Id) from the keyed initial stream (the paper leaves the start arbitrary).
     Returns (X_T in the order of chain_ids, total windows over chains, total rejections)."""
     ids0 = np.arange(B, dtype=np.int64) if chain_ids is None else np.asarray(chain_ids, dtype=np.int64)
     ids = ids0.copy()
@@ -138,7 +144,7 @@ def ula_sample(gradE: Grad, B: int, d: int, K: int, T: int, gamma: float, seed: 
     chain_windows = 0
     rejections = 0
     while n.size:
-        x_out, adv, rej, _, _ = ula_window(gradE, x, n, ids, K, T, gamma, seed, grad_proxy)
+        x_out, adv, rej, _, _ = ula_window(gradE, x, n, ids, K, T, gamma, seed, grad_proxy, tau)
         chain_windows += n.size
         rejections += int(rej.sum())
         n = n + adv

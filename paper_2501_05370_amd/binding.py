@@ -42,6 +42,7 @@ _SIGNATURES = {
     "sd_set_draft_mode": (c_int, [c_void_p, c_int]),
     "sd_set_temperature": (c_int, [c_void_p, c_float]),
     "sd_set_active_count": (c_int, [c_void_p, c_void_p]),
+    "sd_set_verify_shape": (c_int, [c_void_p, c_int32]),
     "sd_workspace_bytes": (c_size_t, [c_void_p, c_int32]),
     "sd_set_workspace": (c_int, [c_void_p, c_void_p, c_size_t]),
     "sd_init_state": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]),
@@ -63,6 +64,9 @@ _SIGNATURES = {
     "sd_langevin_run_phi4": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_int32, c_float, c_float,
                                      c_int32] + [c_void_p] * 4),
     "sd_last_error": (c_char_p, [c_void_p]),
+    # sd_measure.h
+    "sd_measure_stream": (c_int, [c_void_p, c_void_p, c_size_t, c_int32, c_int32, c_void_p]),
+    "sd_measure_mfma": (c_int, [c_int32, c_int32, c_int32, c_void_p, POINTER(ctypes.c_double), c_void_p]),
     # sdden.h
     "sdden_gmm_create": (c_int, [c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_int32, c_void_p,
                                  POINTER(c_void_p)]),
@@ -170,6 +174,9 @@ class Context:
 
     def sd_set_temperature(self, tau: float):
         self._check(self._lib.sd_set_temperature(self._h, tau), "sd_set_temperature")
+
+    def sd_set_verify_shape(self, shape: int):
+        self._check(self._lib.sd_set_verify_shape(self._h, shape), "sd_set_verify_shape")
 
     def sd_set_active_count(self, count: Optional[torch.Tensor]):
         ptr = _dev(count, torch.int32, "count", allow_none=True)
@@ -386,3 +393,21 @@ class Denoiser:
             self.close()
         except Exception:
             pass
+
+
+def sd_measure_stream(src: Optional[torch.Tensor], dst: torch.Tensor, nbytes: int, mode: int, workgroups: int = 0):
+    """Measurement kernel (include/sd_measure.h): streaming copy (0), read (1) or fill (2) of nbytes."""
+    lib = load_library()
+    rc = lib.sd_measure_stream(None if src is None else src.data_ptr(), dst.data_ptr(), nbytes, mode, workgroups, _stream())
+    if rc != 0:
+        raise SDError(f"sd_measure_stream failed ({rc})")
+
+
+def sd_measure_mfma(shape: int, iters: int, sink: torch.Tensor, workgroups: int = 0) -> float:
+    """Measurement kernel (include/sd_measure.h): a loop of MFMAs on register operands; returns its flops."""
+    lib = load_library()
+    fl = ctypes.c_double()
+    rc = lib.sd_measure_mfma(shape, iters, workgroups, sink.data_ptr(), ctypes.byref(fl), _stream())
+    if rc != 0:
+        raise SDError(f"sd_measure_mfma failed ({rc})")
+    return fl.value

@@ -257,17 +257,20 @@ __global__ __launch_bounds__(256) void reduce_gain_kernel(const float* __restric
   *reinterpret_cast<float4*>(P + o) = r;
 }
 
+// Raises the kernel's dynamic-LDS limit on the current device; done for every instantiation when a denoiser is
+// created, never on the launch path (no one-time calls or "already done" flags between a caller and its launches:
+// a HIP graph can capture the very first use).
+template <int BM, int BN, int WM, int WN, int STAGE, int NS>
+hipError_t prepare() {
+  constexpr size_t shmem = NS * static_cast<size_t>(BM + BN) * 128;
+  static_assert(NS >= 2 && shmem <= 160 * 1024, "ring must fit the 160 KiB of LDS");
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, STAGE, NS>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
+}
+
 template <int BM, int BN, int WM, int WN, int STAGE, int NS>
 hipError_t launch(const Args& a, int Rmax, int nsplit, hipStream_t st) {
   constexpr size_t shmem = NS * static_cast<size_t>(BM + BN) * 128;
-  static_assert(NS >= 2 && shmem <= 160 * 1024, "ring must fit the 160 KiB of LDS");
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kernel<BM, BN, WM, WN, STAGE, NS>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   const int tiles = ((Rmax + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   hipLaunchKernelGGL((kernel<BM, BN, WM, WN, STAGE, NS>), dim3(tiles, nsplit), dim3(64 * WM * WN), shmem, st, a);
   return hipGetLastError();

@@ -14,10 +14,12 @@ struct sd_ctx {
   uint64_t seed = 0;
   int mode = SD_DRAFT_FROZEN;
   double tau = 1.0;
+  int verify_shape = 0;         // 0 = default launch shape of the verify kernel, else a measured alternative
   float* dev_a = nullptr;       // [T] each, one allocation of 3T floats
   float* dev_c = nullptr;
   float* dev_sigma = nullptr;
-  int32_t* dev_queue = nullptr;  // [2] zeroed counters behind the schedule (chain dispenser of the Langevin kernel)
+  int32_t* dev_queue = nullptr;  // counter behind the schedule: chain dispenser of the Langevin wavefront kernel
+  int cus = 256;                 // compute units of the context's device
   const int32_t* active = nullptr;
   const float* carry_src = nullptr;    // FROZEN_REUSED: predictions [B,K+1,d] of the window just verified
   float* carry_dst = nullptr;          //   and the [B,d] frozen predictions sd_advance fills for the next one
@@ -48,6 +50,8 @@ inline int fail(std::string& slot, int code, const char* fmt, ...) {
     if (e_ != hipSuccess)                                                               \
       return sdi::fail(slot, SD_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
+
+hipError_t langevin_prepare(int* cus);   // sd_langevin.hip: kernel attributes + CU count, once per sd_create
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

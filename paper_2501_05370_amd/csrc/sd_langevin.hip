@@ -39,7 +39,7 @@ struct LangevinArgs {
   uint8_t* rej;
   float *logratio, *logu;
   const int32_t* active;
-  int32_t* queue;       // [2] chain dispenser of the wavefront kernel: next chain, wavefronts that have left
+  int32_t* queue;       // chain dispenser of the wavefront kernel: the next chain to hand out (zeroed ahead of the launch)
   int max_windows;      // 1: one window per chain (sd_langevin_window); > 1: windows back to back (sd_langevin_run)
   int32_t* n_out;       // run mode: the step each chain reached
   unsigned long long* counters;   // run mode, optional: sum adv, chain-windows, rejections, launches, sum Kt
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void langevin_window_kernel(LangevinArgs 
       for (int w = 0; w < kWaves; ++w) { S1 += sh_part[w][MMAX]; S2 += sh_part[w][MMAX + 1]; }
       lr = (-S1 - 0.5 * S2) * p.inv_tau;
       lu = sdrng::log_uniform(p.seed, id, k1);
-      reject = !(S2 == 0.0 || lu <= fmin(0.0, lr));
+      reject = !(S2 == 0.0 || (lr == lr && lu <= fmin(0.0, lr)));   // a log-ratio that is not a number rejects
       coef = S2 > 0.0 ? S1 / S2 : 0.0;
     } else {
       lu = sdrng::log_uniform(p.seed, id, k1);
@@ -442,7 +442,7 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
         }
       const double S1 = wave_sum(a1), S2 = wave_sum(a2);
       lr = (-S1 - 0.5 * S2) * p.inv_tau;
-      reject = !(S2 == 0.0 || lu <= fmin(0.0, lr));
+      reject = !(S2 == 0.0 || (lr == lr && lu <= fmin(0.0, lr)));   // a log-ratio that is not a number rejects
       coef = S2 > 0.0 ? S1 / S2 : 0.0;
     }
     if (lane == 0) {
@@ -500,46 +500,36 @@ __global__ __launch_bounds__(64 * kWaveChains, 2) void langevin_window_wave_kern
       if (own[c][e]) p.x_out[static_cast<int64_t>(b) * d + i0 + e] = static_cast<float>(cur[c][e]);
   }
   }                                                        // next chain of this wavefront
-  // The last wavefront to leave rewinds the dispenser for the next launch: every other wavefront drew its
-  // final ticket before it counted itself out.
   if (run && p.counters && lane == 0 && acc_win) {
     atomicAdd(&p.counters[0], acc_adv);
     atomicAdd(&p.counters[1], acc_win);
     atomicAdd(&p.counters[2], acc_rej);
     atomicAdd(&p.counters[4], acc_kt);
   }
-  if (lane == 0) {
-    const int total = static_cast<int>(gridDim.x) * kWaveChains;
-    if (atomicAdd(&p.queue[1], 1) == total - 1) {
-      atomicExch(&p.queue[0], 0);
-      atomicExch(&p.queue[1], 0);
-    }
-  }
 }
+
+// The chain dispenser starts every launch at zero: a one-thread kernel ahead of the launch (a kernel, not a
+// memset, so that the sequence can be captured in a HIP graph), never a rewind at the end of the previous one --
+// a launch that does not run to its end must not leave the next call without chains.
+__global__ void reset_dispenser_kernel(int32_t* queue) { queue[0] = 0; }
 
 // run mode: one launch counts as one entry of the `windows` counter
 __global__ void bump_launches_kernel(unsigned long long* counters) { counters[3] += 1; }
 
 template <int CPT, bool WHOLE, bool RUN>
-hipError_t launch_wave(const LangevinArgs& p, int dpad, hipStream_t st) {
+hipError_t prepare_wave() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&langevin_window_wave_kernel<CPT, WHOLE, RUN>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+}
+
+// prepare_wave<...>() has run for every instantiation when the context was created (sdi::langevin_prepare);
+// `resident` = workgroups the chip holds at once (one per CU), from the same call.
+template <int CPT, bool WHOLE, bool RUN>
+hipError_t launch_wave(const LangevinArgs& p, int dpad, int resident, hipStream_t st) {
   const size_t shmem = sizeof(double) * kWaveM * static_cast<size_t>(256 * CPT);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&langevin_window_wave_kernel<CPT, WHOLE, RUN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  static int resident = 0;                                 // workgroups the chip holds at once (1 per CU)
-  if (resident == 0) {
-    int dev = 0, cus = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
-    resident = cus > 0 ? cus : 256;
-  }
   const int groups = (p.B + kWaveChains - 1) / kWaveChains;
   const unsigned grid = static_cast<unsigned>(groups < resident ? groups : resident);
+  hipLaunchKernelGGL(reset_dispenser_kernel, dim3(1), dim3(1), 0, st, p.queue);
   hipLaunchKernelGGL((langevin_window_wave_kernel<CPT, WHOLE, RUN>), dim3(grid), dim3(64 * kWaveChains), shmem, st, p, dpad);
   return hipGetLastError();
 }
@@ -662,7 +652,7 @@ __global__ __launch_bounds__(256) void phi4_window_kernel(Phi4Args p) {
       }
       const double S1 = group_sum_f64<G>(a1), S2 = group_sum_f64<G>(a2);
       lr = (-S1 - 0.5 * S2) * p.inv_tau;
-      reject = alive && !(S2 == 0.0 || lu <= fmin(0.0, lr));
+      reject = alive && !(S2 == 0.0 || (lr == lr && lu <= fmin(0.0, lr)));
       coef = S2 > 0.0 ? S1 / S2 : 0.0;
     }
     if (alive && gl == 0) {
@@ -803,7 +793,7 @@ __global__ __launch_bounds__(256) void phi4_run_kernel(Phi4Args p) {
         }
         const double S1 = group_sum_f64<G>(a1), S2 = group_sum_f64<G>(a2);
         const double lr = (-S1 - 0.5 * S2) * p.inv_tau;
-        rejected = !(S2 == 0.0 || lu <= fmin(0.0, lr));
+        rejected = !(S2 == 0.0 || (lr == lr && lu <= fmin(0.0, lr)));
         const double coef = S2 > 0.0 ? S1 / S2 : 0.0;
         if (rejected) {
 #pragma unroll
@@ -867,6 +857,24 @@ hipError_t launch_phi4(const Phi4Args& p, hipStream_t st) {
 
 }  // namespace
 
+// One-time set-up on the current device, called by sd_create: dynamic-LDS limits of every instantiation of the
+// wavefront kernel (so that no launch path carries set-up calls or "already done" flags) and the CU count.
+hipError_t sdi::langevin_prepare(int* cus) {
+  hipError_t e = hipSuccess;
+#define SD_PREP(c_) \
+  if (e == hipSuccess) e = prepare_wave<c_, false, false>(); \
+  if (e == hipSuccess) e = prepare_wave<c_, false, true>();  \
+  if (e == hipSuccess) e = prepare_wave<c_, true, false>();  \
+  if (e == hipSuccess) e = prepare_wave<c_, true, true>();
+  SD_PREP(1) SD_PREP(2) SD_PREP(3) SD_PREP(4)
+#undef SD_PREP
+  int dev = 0, n = 0;
+  if (e == hipSuccess) e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+  *cus = n > 0 ? n : 256;
+  return e;
+}
+
 namespace {
 
 // Shared by sd_langevin_window (max_windows = 1) and sd_langevin_run.
@@ -894,22 +902,22 @@ int langevin_launch(const char* who, sd_ctx* ctx, int32_t B, const float* x, con
     const bool whole = ctx->d % 4 == 0;
     const int sel = ((groups + 63) / 64 - 1) * 4 + (whole ? 2 : 0) + (max_windows > 1 ? 1 : 0);
     switch (sel) {
-      case 0: e = launch_wave<1, false, false>(p, dpad, st); break;
-      case 1: e = launch_wave<1, false, true>(p, dpad, st); break;
-      case 2: e = launch_wave<1, true, false>(p, dpad, st); break;
-      case 3: e = launch_wave<1, true, true>(p, dpad, st); break;
-      case 4: e = launch_wave<2, false, false>(p, dpad, st); break;
-      case 5: e = launch_wave<2, false, true>(p, dpad, st); break;
-      case 6: e = launch_wave<2, true, false>(p, dpad, st); break;
-      case 7: e = launch_wave<2, true, true>(p, dpad, st); break;
-      case 8: e = launch_wave<3, false, false>(p, dpad, st); break;
-      case 9: e = launch_wave<3, false, true>(p, dpad, st); break;
-      case 10: e = launch_wave<3, true, false>(p, dpad, st); break;
-      case 11: e = launch_wave<3, true, true>(p, dpad, st); break;
-      case 12: e = launch_wave<4, false, false>(p, dpad, st); break;
-      case 13: e = launch_wave<4, false, true>(p, dpad, st); break;
-      case 14: e = launch_wave<4, true, false>(p, dpad, st); break;
-      default: e = launch_wave<4, true, true>(p, dpad, st); break;
+      case 0: e = launch_wave<1, false, false>(p, dpad, ctx->cus, st); break;
+      case 1: e = launch_wave<1, false, true>(p, dpad, ctx->cus, st); break;
+      case 2: e = launch_wave<1, true, false>(p, dpad, ctx->cus, st); break;
+      case 3: e = launch_wave<1, true, true>(p, dpad, ctx->cus, st); break;
+      case 4: e = launch_wave<2, false, false>(p, dpad, ctx->cus, st); break;
+      case 5: e = launch_wave<2, false, true>(p, dpad, ctx->cus, st); break;
+      case 6: e = launch_wave<2, true, false>(p, dpad, ctx->cus, st); break;
+      case 7: e = launch_wave<2, true, true>(p, dpad, ctx->cus, st); break;
+      case 8: e = launch_wave<3, false, false>(p, dpad, ctx->cus, st); break;
+      case 9: e = launch_wave<3, false, true>(p, dpad, ctx->cus, st); break;
+      case 10: e = launch_wave<3, true, false>(p, dpad, ctx->cus, st); break;
+      case 11: e = launch_wave<3, true, true>(p, dpad, ctx->cus, st); break;
+      case 12: e = launch_wave<4, false, false>(p, dpad, ctx->cus, st); break;
+      case 13: e = launch_wave<4, false, true>(p, dpad, ctx->cus, st); break;
+      case 14: e = launch_wave<4, true, false>(p, dpad, ctx->cus, st); break;
+      default: e = launch_wave<4, true, true>(p, dpad, ctx->cus, st); break;
     }
     if (e != hipSuccess) return sdi::fail(ctx->err, SD_ERR_HIP, "%s: %s", who, hipGetErrorString(e));
     if (max_windows > 1 && counters) hipLaunchKernelGGL(bump_launches_kernel, dim3(1), dim3(1), 0, st, p.counters);

@@ -16,7 +16,6 @@
 namespace {
 
 constexpr int kBlock = 256;   // threads per workgroup (4 wavefronts of 64)
-constexpr int kJC = 4;        // window positions reduced together in the verify kernel
 
 std::string g_create_error;
 
@@ -276,16 +275,22 @@ __global__ __launch_bounds__(kBlock) void draft_step_kernel(DraftStepArgs p) {
 // ---------------------------------------------------------------------------------------------
 // Accept test, first rejection, reflection.
 //
-// TPC threads cooperate on one chain (kBlock/TPC chains per workgroup).  Pass 1 streams the
-// chain's K rows of drafts and target predictions once: a thread owns a set of columns and
-// walks the window positions, keeping the previous row in registers, and accumulates the two
-// dot products of every position in fp64.  The per-position sums are reduced with wavefront
-// shuffles (and LDS across wavefronts), the first kJC lanes of the chain run the accept test of
-// one position each, and a ballot finds the first rejection; the chunks of kJC positions after it
-// are not read (unless the per-position diagnostics are asked for).  Pass 2 re-reads only the
-// rejected row and writes the reflected state (or copies the last draft).
+// TPC threads cooperate on one chain (one chain per workgroup from 256 threads up, several below).  Pass 1
+// streams the chain's rows of drafts and target predictions: a thread owns a set of 16-byte columns and walks
+// the window positions JC at a time, keeping the previous row in registers, and accumulates the two dot products
+// of every position in fp64.  The per-position sums are reduced with wavefront exchanges (and LDS across
+// wavefronts), the first JC lanes of the chain run the accept test of one position each, and a ballot finds the
+// first rejection; the groups of JC positions after it are not read (unless the per-position diagnostics are
+// asked for).  Pass 2 re-reads only the rejected row and writes the reflected state (or copies the last draft).
 //
-// All loop bounds depend on K only, so every barrier and shuffle is reached by all threads.
+// What bounds the kernel once the first groups of all chains have streamed is the chain with the latest
+// rejection: its groups are dependent steps (load, reduce, decide).  Hence the loads of UNR columns are requested
+// together before any arithmetic, the logs of the window's accept-test uniforms are drawn once up front by one
+// lane per position, off the steps' critical path, and 512 threads share a chain at d = 12288 (two workgroups
+// per CU keep all 512 chains resident; 1024 threads per chain leave one workgroup per CU, whose load and reduce
+// phases then have nothing to overlap with, and measured slower).
+//
+// Loop bounds depend on K and on per-workgroup flags only, so every barrier and shuffle is reached by all threads.
 // ---------------------------------------------------------------------------------------------
 struct VerifyArgs {
   const float *y, *D0mp, *Dq, *Ytil;
@@ -305,166 +310,235 @@ struct VerifyArgs {
   double inv_tau;
 };
 
-template <int TPC, int VEC, bool FROZEN>
-__global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
-  constexpr int CPW = kBlock / TPC;                 // chains per workgroup
-  constexpr int WAVES = TPC / 64;                   // wavefronts per chain (0: sub-wavefront)
+// Shared state of one chain's threads during pass 1.
+template <int CPW, int WMAX>
+struct VerifyShared {
+  double part[WMAX][16];                 // per-wavefront partial sums of a group (2 * JC <= 16)
+  int jr[CPW];                           // first rejected position so far, -1 = none
+  double coef[CPW];                      // Z.Delta / |Delta|^2 at that position
+  double lu[CPW][SD_MAX_WINDOW];         // log u of every window position
+};
+
+// Per-chain constants of pass 1.
+struct VerifyChain {
+  int b, n, Kt, ncol, slot, t;
+  bool valid, skip0, need_all;
+  int64_t rowB, winB, yoff;
+};
+
+// Positions jc .. jc+JC-1 of one chain: stream their rows (UNR columns per thread requested together), reduce
+// the two dot products of every position, run the accept tests and record the first rejection.  Every thread
+// of the workgroup calls this with the same jc (it holds workgroup barriers).
+template <int TPC, int VEC, bool FROZEN, int JC, int UNR, typename Shared>
+__device__ __forceinline__ void verify_group(const VerifyArgs& p, const VerifyChain& c, Shared& sh, int jc) {
+  constexpr int WAVES = TPC / 64;
   constexpr int WIDTH = TPC < 64 ? TPC : 64;
-  static_assert(TPC >= kJC, "one lane per window position of a chunk");
-
-  __shared__ double sh_part[WAVES > 1 ? WAVES : 1][2 * kJC];
-  __shared__ int sh_jr[CPW];
-  __shared__ double sh_coef[CPW];
-
-  const int slot = TPC == kBlock ? 0 : threadIdx.x / TPC;     // whole workgroup on one chain: uniform
-  const int t = threadIdx.x % TPC;
-  const int b_raw = blockIdx.x * CPW + slot;
-  const int Bact = active_chains(p.active, p.B);
-  const bool valid = b_raw < Bact;
-  const int b = valid ? b_raw : 0;
-  const int n = valid ? p.n[b] : 0;
-  const int Kt = valid ? max(0, min(p.K, p.T - n)) : 0;
-  const int64_t id = valid ? p.id[b] : 0;
-  const int ncol = p.d / VEC;
-  const int64_t rowB = static_cast<int64_t>(b) * p.d;            // offset of y[b], D0[b]
-  const int64_t winB = static_cast<int64_t>(b) * p.rs * p.d;     // offset of the chain's rows in Ytil, Dq
-  const int64_t yoff = static_cast<int64_t>(p.roff) * p.d;       // first draft within the chain's rows of Ytil
-  const bool skip0 = FROZEN && p.first_exact;
-  const bool need_all = p.logratio != nullptr || p.logu != nullptr;
-
-  if (t == 0) sh_jr[slot] = -1;
-  __syncthreads();
-
-  for (int jc = 0; jc < p.K; jc += kJC) {
-    float ak[kJC], ck[kJC];
+  constexpr int MU = FROZEN ? 1 : UNR, MJ = FROZEN ? 1 : JC;   // the explicit draft means are loaded like the drafts
+  static_assert(TPC >= JC && 2 * JC <= 16, "one lane per window position of a group");
+  const int t = c.t, n = c.n, Kt = c.Kt, slot = c.slot;
+  float ak[JC], ck[JC];
 #pragma unroll
-    for (int jj = 0; jj < kJC; ++jj) {
-      const bool in = jc + jj < Kt;
-      ak[jj] = in ? p.a[n + jc + jj] : 0.f;
-      ck[jj] = in ? p.c[n + jc + jj] : 0.f;
-    }
-    double s1[kJC], s2[kJC];
+  for (int jj = 0; jj < JC; ++jj) {
+    const bool in = jc + jj < Kt;
+    ak[jj] = in ? p.a[n + jc + jj] : 0.f;
+    ck[jj] = in ? p.c[n + jc + jj] : 0.f;
+  }
+  double s1[JC], s2[JC];
 #pragma unroll
-    for (int jj = 0; jj < kJC; ++jj) s1[jj] = s2[jj] = 0.0;
+  for (int jj = 0; jj < JC; ++jj) s1[jj] = s2[jj] = 0.0;
 
-    // a chunk after the chain's first rejection decides nothing: it is streamed only when the caller asked
-    // for the per-position log-ratios (sh_jr was last written before the barrier that ended the previous chunk)
-    if (jc < Kt && (need_all || sh_jr[slot] < 0)) {
-      for (int col = t; col < ncol; col += TPC) {
+  // a group after the chain's first rejection decides nothing: it is streamed only when the caller asked
+  // for the per-position log-ratios (jr was last written before the barrier that ended the previous group)
+  if (jc < Kt && (c.need_all || sh.jr[slot] < 0)) {
+    const float* prow = jc == 0 ? p.y + c.rowB : p.Ytil + c.winB + c.yoff + static_cast<int64_t>(jc - 1) * p.d;
+    for (int col0 = t; col0 < c.ncol; col0 += TPC * UNR) {
+      Pack<VEC> prev[UNR], d0[UNR], cur[UNR][JC], dq[UNR][JC], mp[MU][MJ];
+      // every load of the UNR columns is requested before the first product
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int col = col0 + u * TPC;
+        if (UNR > 1 && col >= c.ncol) continue;
         const int64_t off = static_cast<int64_t>(col) * VEC;
-        Pack<VEC> prev, d0;
-        if (jc == 0) prev.load(p.y + rowB + off);
-        else prev.load(p.Ytil + winB + yoff + static_cast<int64_t>(jc - 1) * p.d + off);
-        if (FROZEN) d0.load(p.D0mp + rowB + off);
+        prev[u].load(prow + off);
+        if (FROZEN) d0[u].load(p.D0mp + c.rowB + off);
 #pragma unroll
-        for (int jj = 0; jj < kJC; ++jj) {
+        for (int jj = 0; jj < JC; ++jj) {
           const int j = jc + jj;
           if (j < Kt) {
-            const int64_t r = winB + static_cast<int64_t>(j) * p.d + off;
-            Pack<VEC> cur, dq, mp;
-            cur.load(p.Ytil + r + yoff);
+            const int64_t r = c.winB + static_cast<int64_t>(j) * p.d + off;
+            cur[u][jj].load(p.Ytil + r + c.yoff);
             if (FROZEN) {
-              if (j > 0 || !skip0) dq.load(p.Dq + r);
+              if (j > 0 || !c.skip0) dq[u][jj].load(p.Dq + r);
             } else {
-              if (j == 0 && p.Dq0) dq.load(p.Dq0 + rowB + off);
-              else dq.load(p.Dq + r);
-              mp.load(p.D0mp + r);
+              if (j == 0 && p.Dq0) dq[u][jj].load(p.Dq0 + c.rowB + off);
+              else dq[u][jj].load(p.Dq + r);
+              mp[FROZEN ? 0 : u][FROZEN ? 0 : jj].load(p.D0mp + r);
             }
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int col = col0 + u * TPC;
+        if (UNR > 1 && col >= c.ncol) continue;
+#pragma unroll
+        for (int jj = 0; jj < JC; ++jj) {
+          const int j = jc + jj;
+          if (j < Kt) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
               double w, dl;      // w = sigma*Z, dl = (sigma/c)*Delta (FROZEN) or sigma*Delta
+              const float pv = jj == 0 ? prev[u].v[e] : cur[u][jj > 0 ? jj - 1 : 0].v[e];
               if (FROZEN) {
-                w = static_cast<double>(cur.v[e]) - static_cast<double>(ak[jj]) * prev.v[e] -
-                    static_cast<double>(ck[jj]) * d0.v[e];
-                dl = (j > 0 || !skip0) ? static_cast<double>(d0.v[e]) - static_cast<double>(dq.v[e]) : 0.0;
+                w = static_cast<double>(cur[u][jj].v[e]) - static_cast<double>(ak[jj]) * pv -
+                    static_cast<double>(ck[jj]) * d0[u].v[e];
+                dl = (j > 0 || !c.skip0) ? static_cast<double>(d0[u].v[e]) - static_cast<double>(dq[u][jj].v[e]) : 0.0;
               } else {
-                w = static_cast<double>(cur.v[e]) - static_cast<double>(mp.v[e]);
-                dl = static_cast<double>(mp.v[e]) - (static_cast<double>(ak[jj]) * prev.v[e] +
-                                                     static_cast<double>(ck[jj]) * dq.v[e]);
+                const float m = mp[FROZEN ? 0 : u][FROZEN ? 0 : jj].v[e];
+                w = static_cast<double>(cur[u][jj].v[e]) - static_cast<double>(m);
+                dl = static_cast<double>(m) - (static_cast<double>(ak[jj]) * pv +
+                                               static_cast<double>(ck[jj]) * dq[u][jj].v[e]);
               }
               s1[jj] = fma(w, dl, s1[jj]);
               s2[jj] = fma(dl, dl, s2[jj]);
             }
-            prev = cur;
           }
         }
       }
     }
+  }
 
-    // ---- reduce the 2*kJC sums over the chain's threads
-    double mine1 = 0.0, mine2 = 0.0;      // lane t < kJC ends up with the sums of position jc+t
+  // ---- reduce the 2*JC sums over the chain's threads
+  double mine1 = 0.0, mine2 = 0.0;      // lane t < JC ends up with the sums of position jc+t
 #pragma unroll
-    for (int jj = 0; jj < kJC; ++jj) {
-      s1[jj] = group_sum<WIDTH>(s1[jj]);
-      s2[jj] = group_sum<WIDTH>(s2[jj]);
-    }
-    if (WAVES > 1) {
-      const int wave = t / 64;
-      if ((t & 63) == 0) {
+  for (int jj = 0; jj < JC; ++jj) {
+    s1[jj] = group_sum<WIDTH>(s1[jj]);
+    s2[jj] = group_sum<WIDTH>(s2[jj]);
+  }
+  if (WAVES > 1) {
+    const int wave = t / 64;
+    if ((t & 63) == 0) {
 #pragma unroll
-        for (int jj = 0; jj < kJC; ++jj) {
-          sh_part[wave][jj] = s1[jj];
-          sh_part[wave][kJC + jj] = s2[jj];
-        }
+      for (int jj = 0; jj < JC; ++jj) {
+        sh.part[wave][jj] = s1[jj];
+        sh.part[wave][JC + jj] = s2[jj];
       }
-      __syncthreads();
-      if (t < kJC) {
-#pragma unroll
-        for (int w = 0; w < (WAVES > 1 ? WAVES : 1); ++w) {
-          mine1 += sh_part[w][t];
-          mine2 += sh_part[w][kJC + t];
-        }
-      }
-    } else {
-#pragma unroll
-      for (int jj = 0; jj < kJC; ++jj)
-        if (t == jj) { mine1 = s1[jj]; mine2 = s2[jj]; }
-    }
-
-    // ---- accept test of position j = jc + t by the chain's first kJC lanes
-    bool reject = false;
-    double coef = 0.0;
-    if (t < kJC) {
-      const int j = jc + t;
-      const bool inwin = j < Kt;
-      double lr = 0.0, lu = 0.0;
-      if (inwin) {
-        const int k = n + j;
-        const double sg = p.sigma[k];
-        const double inv_s2 = 1.0 / (sg * sg);
-        double S1, S2;                       // Z.Delta and |Delta|^2
-        if (FROZEN) {
-          const double c = p.c[k];
-          S1 = mine1 * c * inv_s2;
-          S2 = mine2 * c * c * inv_s2;
-        } else {
-          S1 = mine1 * inv_s2;
-          S2 = mine2 * inv_s2;
-        }
-        lr = (-S1 - 0.5 * S2) * p.inv_tau;
-        lu = sdrng::log_uniform(p.seed, id, static_cast<uint32_t>(k + 1));
-        reject = !(S2 == 0.0 || lu <= fmin(0.0, lr));
-        coef = S2 > 0.0 ? S1 / S2 : 0.0;
-      }
-      if (valid && j < p.K) {
-        if (p.logratio) p.logratio[static_cast<int64_t>(b) * p.K + j] = static_cast<float>(lr);
-        if (p.logu) p.logu[static_cast<int64_t>(b) * p.K + j] = static_cast<float>(lu);
-      }
-    }
-    const unsigned long long ballot = __ballot(reject);
-    const int lane = threadIdx.x & 63;
-    const unsigned long long mine =
-        (TPC < 64) ? ((ballot >> (lane & ~(TPC - 1))) & ((1ull << kJC) - 1ull)) : (ballot & ((1ull << kJC) - 1ull));
-    if (t < kJC && reject && sh_jr[slot] < 0 && (mine & ((1ull << t) - 1ull)) == 0ull) {
-      // lowest rejecting position of this chunk, and no earlier chunk rejected
-      sh_jr[slot] = jc + t;
-      sh_coef[slot] = coef;
     }
     __syncthreads();
+    if (t < JC) {
+#pragma unroll
+      for (int w = 0; w < (WAVES > 1 ? WAVES : 1); ++w) {
+        mine1 += sh.part[w][t];
+        mine2 += sh.part[w][JC + t];
+      }
+    }
+  } else {
+#pragma unroll
+    for (int jj = 0; jj < JC; ++jj)
+      if (t == jj) { mine1 = s1[jj]; mine2 = s2[jj]; }
+  }
+
+  // ---- accept test of position j = jc + t by the chain's first JC lanes
+  bool reject = false;
+  double coef = 0.0;
+  if (t < JC) {
+    const int j = jc + t;
+    const bool inwin = j < Kt;
+    double lr = 0.0, lu = 0.0;
+    if (inwin) {
+      const int k = n + j;
+      const double sg = p.sigma[k];
+      const double inv_s2 = 1.0 / (sg * sg);
+      double S1, S2;                       // Z.Delta and |Delta|^2
+      if (FROZEN) {
+        const double cc = p.c[k];
+        S1 = mine1 * cc * inv_s2;
+        S2 = mine2 * cc * cc * inv_s2;
+      } else {
+        S1 = mine1 * inv_s2;
+        S2 = mine2 * inv_s2;
+      }
+      lr = (-S1 - 0.5 * S2) * p.inv_tau;
+      lu = sh.lu[slot][j];
+      // a log-ratio that is not a number (non-finite inputs) counts as a rejection
+      reject = !(S2 == 0.0 || (lr == lr && lu <= fmin(0.0, lr)));
+      coef = S2 > 0.0 ? S1 / S2 : 0.0;
+    }
+    if (c.valid && j < p.K) {
+      if (p.logratio) p.logratio[static_cast<int64_t>(c.b) * p.K + j] = static_cast<float>(lr);
+      if (p.logu) p.logu[static_cast<int64_t>(c.b) * p.K + j] = static_cast<float>(lu);
+    }
+  }
+  const unsigned long long ballot = __ballot(reject);
+  const int lane = threadIdx.x & 63;
+  const unsigned long long mine =
+      (TPC < 64) ? ((ballot >> (lane & ~(TPC - 1))) & ((1ull << JC) - 1ull)) : (ballot & ((1ull << JC) - 1ull));
+  if (t < JC && reject && sh.jr[slot] < 0 && (mine & ((1ull << t) - 1ull)) == 0ull) {
+    // lowest rejecting position of this group, and no earlier group rejected
+    sh.jr[slot] = jc + t;
+    sh.coef[slot] = coef;
+  }
+  __syncthreads();
+}
+
+// GROUPS: 0 = groups of 4 positions, one column at a time (short rows; the explicit-mean form, which carries one
+// more operand row per position); 1 = groups of 2 positions, 3 columns at a time (the same number of loads
+// outstanding per thread): most chains reject within the first positions, where a small group reads fewer rows
+// past the rejection.  A thread adds its columns in the same order whatever the grouping, so the schedules give
+// bit-identical sums.  Measured and dropped: groups growing 2, 2, 4, 8 (the widest group sets the register count,
+// 157 against 108, and the lost occupancy costs more than the steps save) and 2, 2, then 4 (in the c4 sampler 79.5
+// against 77.3 us per launch: a group of 4 goes one column at a time, and the steps of a long chain are bound by
+// the loads one workgroup keeps in flight, not by their number).
+template <int TPC, int VEC, bool FROZEN, int GROUPS>
+__global__ __launch_bounds__(TPC > kBlock ? TPC : kBlock) void verify_kernel(VerifyArgs p) {
+  constexpr int BLOCK = TPC > kBlock ? TPC : kBlock;
+  constexpr int CPW = BLOCK / TPC;                  // chains per workgroup
+  constexpr int WAVES = TPC / 64;                   // wavefronts per chain (0: sub-wavefront)
+  __shared__ VerifyShared<CPW, (WAVES > 1 ? WAVES : 1)> sh;
+
+  VerifyChain c;
+  c.slot = TPC == BLOCK ? 0 : threadIdx.x / TPC;    // whole workgroup on one chain: uniform
+  c.t = threadIdx.x % TPC;
+  const int b_raw = blockIdx.x * CPW + c.slot;
+  const int Bact = active_chains(p.active, p.B);
+  c.valid = b_raw < Bact;
+  c.b = c.valid ? b_raw : 0;
+  c.n = c.valid ? p.n[c.b] : 0;
+  c.Kt = c.valid ? max(0, min(p.K, p.T - c.n)) : 0;
+  const int64_t id = c.valid ? p.id[c.b] : 0;
+  c.ncol = p.d / VEC;
+  c.rowB = static_cast<int64_t>(c.b) * p.d;                  // offset of y[b], D0[b]
+  c.winB = static_cast<int64_t>(c.b) * p.rs * p.d;           // offset of the chain's rows in Ytil, Dq
+  c.yoff = static_cast<int64_t>(p.roff) * p.d;               // first draft within the chain's rows of Ytil
+  c.skip0 = FROZEN && p.first_exact;
+  c.need_all = p.logratio != nullptr || p.logu != nullptr;
+  const int t = c.t, slot = c.slot, n = c.n, Kt = c.Kt, b = c.b, ncol = c.ncol;
+  const bool valid = c.valid;
+  const int64_t rowB = c.rowB, winB = c.winB, yoff = c.yoff;
+
+  if (t == 0) sh.jr[slot] = -1;
+  for (int j = t; j < Kt; j += TPC)
+    sh.lu[slot][j] = sdrng::log_uniform(p.seed, id, static_cast<uint32_t>(n + j + 1));
+  __syncthreads();
+
+  // With the whole workgroup on one chain the walk ends at the chain's first rejection (uniform: every thread
+  // reads the same flag behind the group's closing barrier) unless the diagnostics want every position; where
+  // several chains share a workgroup the later groups only cost their barriers.
+  constexpr bool kLeave = TPC == BLOCK;
+  if constexpr (GROUPS == 0) {
+    for (int jc = 0; jc < p.K; jc += 4) {
+      verify_group<TPC, VEC, FROZEN, 4, 1>(p, c, sh, jc);
+      if (kLeave && !c.need_all && sh.jr[slot] >= 0) break;
+    }
+  } else {
+    for (int jc = 0; jc < p.K; jc += 2) {
+      verify_group<TPC, VEC, FROZEN, 2, 3>(p, c, sh, jc);
+      if (kLeave && !c.need_all && sh.jr[slot] >= 0) break;
+    }
   }
 
   // ---- pass 2: write the state the chain keeps
-  const int jr = sh_jr[slot];
+  const int jr = sh.jr[slot];
   if (!valid) return;
   if (t == 0) {
     p.adv[b] = jr >= 0 ? jr + 1 : Kt;
@@ -481,23 +555,40 @@ __global__ __launch_bounds__(kBlock) void verify_kernel(VerifyArgs p) {
     return;
   }
   const int k = n + jr;
-  const double a = p.a[k], c = p.c[k];
-  const double two_coef = 2.0 * sh_coef[slot];
-  const float* prevrow = jr == 0 ? p.y + rowB : p.Ytil + winB + yoff + static_cast<int64_t>(jr - 1) * p.d;
+  const double a = p.a[k], cc = p.c[k];
+  const double two_coef = 2.0 * sh.coef[slot];
   const int64_t r = winB + static_cast<int64_t>(jr) * p.d;
+  if (FROZEN) {
+    // Y = m^q + sigma (Z - 2 (Z.Delta/|Delta|^2) Delta) with sigma Z = y~ - m^p and sigma Delta = m^p - m^q =
+    // c (D0 - Dq): the a * (previous state) terms cancel, Y = y~ - c (1 + 2 Z.Delta/|Delta|^2) (D0 - Dq)
+    const double f = cc * (1.0 + two_coef);
+    for (int col = t; col < ncol; col += TPC) {
+      const int64_t off = static_cast<int64_t>(col) * VEC;
+      Pack<VEC> cur, dq, x, o;
+      cur.load(p.Ytil + r + yoff + off);
+      dq.load(p.Dq + r + off);
+      x.load(p.D0mp + rowB + off);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        o.v[e] = static_cast<float>(static_cast<double>(cur.v[e]) -
+                                    f * (static_cast<double>(x.v[e]) - static_cast<double>(dq.v[e])));
+      o.store(dst + off);
+    }
+    return;
+  }
+  const float* prevrow = jr == 0 ? p.y + rowB : p.Ytil + winB + yoff + static_cast<int64_t>(jr - 1) * p.d;
   for (int col = t; col < ncol; col += TPC) {
     const int64_t off = static_cast<int64_t>(col) * VEC;
     Pack<VEC> prev, cur, dq, x, o;
     prev.load(prevrow + off);
     cur.load(p.Ytil + r + yoff + off);
-    if (!FROZEN && jr == 0 && p.Dq0) dq.load(p.Dq0 + rowB + off);
+    if (jr == 0 && p.Dq0) dq.load(p.Dq0 + rowB + off);
     else dq.load(p.Dq + r + off);
-    if (FROZEN) x.load(p.D0mp + rowB + off);
-    else x.load(p.D0mp + r + off);
+    x.load(p.D0mp + r + off);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
-      const double mq = a * prev.v[e] + c * dq.v[e];
-      const double mp = FROZEN ? a * prev.v[e] + c * x.v[e] : static_cast<double>(x.v[e]);
+      const double mq = a * prev.v[e] + cc * dq.v[e];
+      const double mp = static_cast<double>(x.v[e]);
       // Y = m^q + sigma (Z - 2 (Z.Delta/|Delta|^2) Delta),  sigma Z = cur - m^p, sigma Delta = m^p - m^q
       o.v[e] = static_cast<float>(mq + (static_cast<double>(cur.v[e]) - mp) - two_coef * (mp - mq));
     }
@@ -678,12 +769,29 @@ hipError_t static_scratch(int device, void** out) {
   return hipSuccess;
 }
 
-template <int TPC, int VEC>
+template <int TPC, int VEC, int GROUPS>
 void launch_verify(bool frozen, int B, hipStream_t st, const VerifyArgs& p) {
-  constexpr int CPW = kBlock / TPC;
+  constexpr int BLOCK = TPC > kBlock ? TPC : kBlock;
+  constexpr int CPW = BLOCK / TPC;
   const unsigned grid = static_cast<unsigned>((B + CPW - 1) / CPW);
-  if (frozen) hipLaunchKernelGGL((verify_kernel<TPC, VEC, true>), dim3(grid), dim3(kBlock), 0, st, p);
-  else        hipLaunchKernelGGL((verify_kernel<TPC, VEC, false>), dim3(grid), dim3(kBlock), 0, st, p);
+  if (frozen) hipLaunchKernelGGL((verify_kernel<TPC, VEC, true, GROUPS>), dim3(grid), dim3(BLOCK), 0, st, p);
+  else        hipLaunchKernelGGL((verify_kernel<TPC, VEC, false, 0>), dim3(grid), dim3(BLOCK), 0, st, p);
+}
+
+// Launch shape by row length (ncol = 16-byte columns, or elements when the rows are not 16-byte aligned).
+// Rows of more than 256 columns take (threads per chain, positions per group) from `shape`: 0 = the default
+// for the row length, 1..4 = the alternatives it was measured against (sd_set_verify_shape).
+template <int VEC>
+void dispatch_verify(bool frozen, int B, int ncol, int shape, hipStream_t st, const VerifyArgs& p) {
+  if (ncol <= 32) return launch_verify<16, VEC, 0>(frozen, B, st, p);
+  if (ncol <= 256) return launch_verify<64, VEC, 0>(frozen, B, st, p);
+  if (shape == 0) shape = ncol <= 1024 ? 2 : 4;
+  switch (shape) {
+    case 1: return launch_verify<256, VEC, 0>(frozen, B, st, p);
+    case 2: return launch_verify<256, VEC, 1>(frozen, B, st, p);
+    case 3: return launch_verify<512, VEC, 0>(frozen, B, st, p);
+    default: return launch_verify<512, VEC, 1>(frozen, B, st, p);
+  }
 }
 
 }  // namespace
@@ -711,6 +819,7 @@ int sd_create(const sd_schedule* s, int32_t d, int32_t K, sd_ctx** out) {
   ctx->T = s->T; ctx->d = d; ctx->K = K;
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) e = static_scratch(ctx->device, &ctx->static_ws);   // this device's copy of the static scratch
+  if (e == hipSuccess) e = sdi::langevin_prepare(&ctx->cus);
   float* dev = nullptr;
   const size_t sched_floats = (3 * static_cast<size_t>(s->T) + 15) / 16 * 16;   // counters start 64-byte aligned
   if (e == hipSuccess) e = hipMalloc(&dev, sizeof(float) * sched_floats + 64);
@@ -777,6 +886,13 @@ int sd_set_draft_mirror(sd_ctx* ctx, uint16_t* Ytilde_bf16) {
 int sd_set_start_prediction(sd_ctx* ctx, const float* D_start) {
   if (!ctx) return SD_ERR_ARG;
   ctx->start_pred = D_start;
+  return SD_OK;
+}
+
+int sd_set_verify_shape(sd_ctx* ctx, int32_t shape) {
+  if (!ctx) return SD_ERR_ARG;
+  if (shape < 0 || shape > 4) return sdi::fail(ctx->err, SD_ERR_ARG, "sd_set_verify_shape: shape must be 0..4");
+  ctx->verify_shape = shape;
   return SD_OK;
 }
 
@@ -890,15 +1006,8 @@ int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const in
                    sdi::aligned16(Dq) && sdi::aligned16(Ytilde) && sdi::aligned16(y_out);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int ncol = vec ? ctx->d / 4 : ctx->d;
-  if (vec) {
-    if (ncol <= 32)       launch_verify<16, 4>(frozen, B, st, p);
-    else if (ncol <= 256) launch_verify<64, 4>(frozen, B, st, p);
-    else                  launch_verify<256, 4>(frozen, B, st, p);
-  } else {
-    if (ncol <= 32)       launch_verify<16, 1>(frozen, B, st, p);
-    else if (ncol <= 256) launch_verify<64, 1>(frozen, B, st, p);
-    else                  launch_verify<256, 1>(frozen, B, st, p);
-  }
+  if (vec) dispatch_verify<4>(frozen, B, ncol, ctx->verify_shape, st, p);
+  else     dispatch_verify<1>(frozen, B, ncol, ctx->verify_shape, st, p);
   SD_HIP_TRY(ctx->err, hipGetLastError());
   return SD_OK;
 }

@@ -369,7 +369,9 @@ extern "C" int sdden_lowrank_create(int32_t d, int32_t r, const float* mu, const
   LowRankDenoiser* L = new (std::nothrow) LowRankDenoiser;
   if (!L) return sdi::fail(E, SD_ERR_ARG, "sdden_lowrank_create: out of host memory");
   L->d = d; L->T = T; L->r = r; L->rpad = rpad;
-  hipError_t e = hipMalloc(&L->dev, h.size() * sizeof(float));
+  hipError_t e = lrgemm::prepare<128, 128, 2, 2, 1, 2>();   // dynamic-LDS limits of the two GEMM stages
+  if (e == hipSuccess) e = lrgemm::prepare<128, 128, 2, 2, 2, 2>();
+  if (e == hipSuccess) e = hipMalloc(&L->dev, h.size() * sizeof(float));
   if (e == hipSuccess) e = hipMemcpy(L->dev, h.data(), h.size() * sizeof(float), hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     delete L;

@@ -123,10 +123,6 @@ class _SamplerBase:
         b.B_active.fill_(B)
         self._set_active(b.B_active)
         try:
-            if graph and B > 0:                                 # first window eagerly: one-time kernel attribute set-up
-                self.window(B)
-                self.advance(B)
-                B = min(B, int(b.B_active.item()))
             while B > 0:
                 bound = self._bound(B)
                 if graph:

@@ -80,25 +80,31 @@ def test_batch_composition_does_not_change_results():
     assert np.array_equal(sub[[200, 3, 77, 255, 128]], full[[200, 3, 77, 255, 128]])
 
 
-@pytest.mark.parametrize("B,d,M,K,T", [(64, 1000, 16, 16, 40), (40, 10, 3, 5, 12), (32, 1003, 16, 16, 30),
-                                       (16, 2100, 7, 8, 20), (8, 4096, 16, 4, 9),
-                                       # two and three coordinate groups per lane; more chains than the resident
-                                       # wavefronts (each wavefront then takes several chains from the counter)
-                                       (48, 512, 5, 6, 15), (24, 700, 16, 8, 20), (3000, 40, 4, 6, 14)])
-def test_langevin_window_matches_oracle(B, d, M, K, T):
+_LANGEVIN_SHAPES = [(64, 1000, 16, 16, 40), (40, 10, 3, 5, 12), (32, 1003, 16, 16, 30),
+                    (16, 2100, 7, 8, 20), (8, 4096, 16, 4, 9),
+                    # two and three coordinate groups per lane; more chains than the resident
+                    # wavefronts (each wavefront then takes several chains from the counter)
+                    (48, 512, 5, 6, 15), (24, 700, 16, 8, 20), (3000, 40, 4, 6, 14)]
+# every shape at the exact sampler's temperature; one shape per kernel variant at a hotter and a colder one
+_LANGEVIN_CASES = [s + (1.0,) for s in _LANGEVIN_SHAPES] + \
+                  [s + (t,) for s in _LANGEVIN_SHAPES if s[1] in (1000, 2100, 700, 40) for t in (2.0, 0.6)]
+
+
+@pytest.mark.parametrize("B,d,M,K,T,tau", _LANGEVIN_CASES)
+def test_langevin_window_matches_oracle(B, d, M, K, T, tau):
     rng = np.random.default_rng(8)
     cfg = W.make_config("c5", B=B, d=d, M=M, K=K, T=T)
     p = cfg.params
     sc = GMMScore(p)
     gamma = cfg.gamma
-    ctx = make_context(cfg.schedule, d, K, seed=21)
+    ctx = make_context(cfg.schedule, d, K, seed=21, tau=tau)
     # start near / between components so that gradients differ along the window
     comp = rng.integers(0, M, size=B)
     x = as_f32_f64(p.means[comp] * rng.uniform(0.3, 1.0, size=(B, 1)) + rng.standard_normal((B, d)))
     n = rng.integers(0, T, size=B)
     n[:3] = [T - 1, T - 2, 0]
     ids = rng.permutation(max(1000, 2 * B))[:B].astype(np.int64)
-    xo, adv, rej, lr, lu = L.ula_window(sc, x, n, ids, K, T, gamma, seed=21)
+    xo, adv, rej, lr, lu = L.ula_window(sc, x, n, ids, K, T, gamma, seed=21, tau=tau)
     gx = torch.full((B, d), 9.0, dtype=torch.float32, device="cuda")
     gadv = torch.zeros(B, dtype=torch.int32, device="cuda")
     grej = torch.zeros(B, dtype=torch.uint8, device="cuda")
@@ -141,7 +147,8 @@ def test_langevin_free_run_small():
 
 
 @pytest.mark.parametrize("L_,B,K,T", [(8, 300, 20, 50), (4, 70, 6, 30), (16, 40, 12, 40), (5, 33, 7, 25)])
-def test_phi4_langevin_window_matches_oracle(L_, B, K, T):
+@pytest.mark.parametrize("tau", [1.0, 3000.0])       # at tau = 3000 the walk goes past its second position (|Delta|^2 is 200 to 3000 here)
+def test_phi4_langevin_window_matches_oracle(L_, B, K, T, tau):
     """The fused Langevin window on the phi^4 lattice energy against the oracle's ula_window with the
     oracle's Phi4Energy: grids whose sites fill the lanes exactly, leave lanes idle (5 x 5) or take a
     whole wavefront (16 x 16); chains at ragged positions, near the end of the run."""
@@ -151,13 +158,13 @@ def test_phi4_langevin_window_matches_oracle(L_, B, K, T):
     cfg = W.make_config("phi4", B=B, d=d, K=K, T=T)
     beta, gamma = cfg.params.beta, cfg.gamma
     E = Phi4Energy(L_, beta)
-    ctx = make_context(cfg.schedule, d, K, seed=31)
+    ctx = make_context(cfg.schedule, d, K, seed=31, tau=tau)
     # ordered states with noise, the regime the chain lives in
     x = as_f32_f64(rng.choice([-1.0, 1.0], size=(B, 1)) + 0.15 * rng.standard_normal((B, d)))
     n = rng.integers(0, T, size=B)
     n[:3] = [T - 1, T - 2, 0]
     ids = rng.permutation(5000)[:B].astype(np.int64)
-    xo, adv, rej, lr, lu = L.ula_window(E, x, n, ids, K, T, gamma, seed=31)
+    xo, adv, rej, lr, lu = L.ula_window(E, x, n, ids, K, T, gamma, seed=31, tau=tau)
     gx = torch.full((B, d), 9.0, dtype=torch.float32, device="cuda")
     gadv = torch.zeros(B, dtype=torch.int32, device="cuda")
     grej = torch.zeros(B, dtype=torch.uint8, device="cuda")
@@ -169,8 +176,10 @@ def test_phi4_langevin_window_matches_oracle(L_, B, K, T):
         pass
     R.adv, R.logu, R.logratio = adv, lu, lr
     nbad, near = decisions_match(host(gadv), R)
-    print(f"[phi4 L={L_}] rejected {rej.mean():.2f}, mean adv {adv.mean():.2f}, mismatches {nbad} (near ties {near})")
+    print(f"[phi4 L={L_} tau={tau}] rejected {rej.mean():.2f}, mean adv {adv.mean():.2f}, mismatches {nbad} (near ties {near})")
     assert nbad == near
+    if tau > 1.0:
+        assert adv.max() > 3                         # the temperature case does reach later positions
     same = host(gadv) == adv
     assert same.mean() > 0.9
     assert np.array_equal(host(grej)[same].astype(bool), rej[same])
@@ -249,6 +258,30 @@ def test_langevin_run_equals_the_window_loop_and_the_oracle(B, d, M, K, T):
     after = b.counters.tolist()
     assert torch.equal(xo[:B], b.y[:B]) and np.all(host(b.n)[:B] == T)
     assert [after[i] for i in (0, 1, 2, 4)] == [before[i] for i in (0, 1, 2, 4)]
+
+
+@pytest.mark.parametrize("kind,kw,tau", [("c5", dict(B=120, d=200, M=4, K=8, T=40), 2.0),
+                                         ("phi4", dict(B=200, T=60), 400.0)])
+def test_langevin_runs_with_temperature_equal_the_window_loop(kind, kw, tau):
+    """The temperature of the accept test (App. "Influence of the temperature") in the one-launch forms: same
+    results as window + advance repeated, bit for bit, and the acceptance moves the way the temperature says."""
+    from paper_2501_05370_amd.runner import make_sampler
+    cfg = W.make_config(kind, **kw)
+    ids = torch.arange(cfg.B, dtype=torch.int64, device="cuda")
+    res = {}
+    for t in (1.0, tau):
+        outs = []
+        for fused in (False, True):
+            smp = make_sampler(cfg)
+            smp.ctx.sd_set_temperature(t)
+            out, counters = smp.run_fused(ids) if fused else smp.run(ids)
+            outs.append((host(out)[:cfg.B].copy(), counters))
+        (xw, cw), (xf, cf) = outs
+        assert np.array_equal(xw, xf)
+        assert [cf[i] for i in (0, 1, 2, 4)] == [cw[i] for i in (0, 1, 2, 4)]
+        res[t] = cf
+    print(f"[{kind} tau={tau}] chain-windows {res[1.0][1]} -> {res[tau][1]}, rejections {res[1.0][2]} -> {res[tau][2]}")
+    assert res[tau][1] < res[1.0][1] and res[tau][2] < res[1.0][2]      # hotter: fewer rejections, fewer windows
 
 
 @pytest.mark.parametrize("L_,B,K,T", [(8, 300, 20, 50), (4, 70, 6, 30), (16, 40, 12, 40), (5, 33, 7, 25)])

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared():
     names = set()
-    for h in ("sd.h", "sdden.h"):
+    for h in ("sd.h", "sdden.h", "sd_measure.h"):
         text = open(os.path.join(ROOT, "include", h)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names |= set(re.findall(r"\b(sd(?:den)?_[a-z0-9_]+)\s*\(", text))

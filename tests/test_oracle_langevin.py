@@ -34,6 +34,43 @@ def test_ula_window_is_the_general_window_with_langevin_coefficients():
     assert np.array_equal(adv2, res2.adv) and np.allclose(xo2, res2.y_out, atol=1e-6)
 
 
+def test_ula_window_temperature_pins():
+    """The temperature divides the log acceptance ratio (App. "Influence of the temperature"): tau = 1 is the
+    plain window bit for bit; the Langevin window equals the general window with Langevin coefficients at the
+    same tau; a very large tau accepts every draft (the ratio tends to one) and a very small one rejects the
+    first draft whose means differ; decisions move monotonically with tau on fixed random numbers."""
+    rng = np.random.default_rng(5)
+    d, M, K, T, B = 10, 3, 6, 11, 400
+    gamma = float(np.float32(0.05))
+    sc = GMMScore(W.random_gmm(rng, M, d, 1.0, 1.0, 1.0, uniform_weights=False))
+    sched = W.langevin_schedule(T, 0.05)
+    x = rng.standard_normal((B, d)) * 1.5
+    n = rng.integers(0, T, size=B)
+    ids = np.arange(B, dtype=np.int64) * 3 + 1
+    Kt = np.minimum(K, T - n)
+    base = L.ula_window(sc, x, n, ids, K, T, gamma, seed=7)
+    one = L.ula_window(sc, x, n, ids, K, T, gamma, seed=7, tau=1.0)
+    for a, b in zip(base, one):
+        assert np.array_equal(a, b)
+    advs = []
+    for tau in (0.5, 2.0):
+        xo, adv, rej, lr, lu = L.ula_window(sc, x, n, ids, K, T, gamma, seed=7, tau=tau)
+        res, *_ = S.window(sched, lambda v, k: sc(v), x, n, ids, K, seed=7, tau=tau)
+        assert np.array_equal(adv, res.adv) and np.array_equal(rej, res.rejected)
+        assert np.allclose(xo, res.y_out, atol=1e-6) and np.allclose(lr, res.logratio, atol=1e-5)
+        assert np.allclose(lr * tau, base[3], atol=1e-12)            # the same ratio, divided by tau
+        assert np.array_equal(lu, base[4])
+        advs.append(adv)
+    assert np.all(advs[0] <= base[1]) and np.all(base[1] <= advs[1])    # colder rejects sooner, hotter later
+    assert (advs[0] < advs[1]).any()
+    _, adv_hot, rej_hot, _, _ = L.ula_window(sc, x, n, ids, K, T, gamma, seed=7, tau=1e12)
+    assert np.array_equal(adv_hot, Kt) and not rej_hot.any()
+    _, adv_cold, rej_cold, lr_cold, _ = L.ula_window(sc, x, n, ids, K, T, gamma, seed=7, tau=1e-12)
+    # frozen gradient: the first draft is exact (Delta = 0), the second is rejected unless the ratio exceeds one
+    second = Kt >= 2
+    assert np.all(adv_cold[second & (base[3][:, 1] < 0)] == 2)
+
+
 def test_ula_exact_proxy_reproduces_sequential_ula():
     rng = np.random.default_rng(1)
     p = W.random_gmm(rng, 2, 4, 1.0, 1.0, 1.0)
