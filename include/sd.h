@@ -7,7 +7,7 @@
  *     sd_draft   : y~_{n+1..n+Kt} from the frozen draft mean  a_k y~_k + c_k D0      (Sec. 3.1)
  *     Dq_j = D(y~_{n+j-1}, n+j-1)            one batched target call on the drafts  (caller)
  *     sd_verify  : accept test, first rejection, reflection-maximal-coupling resample (Sec. 3.3)
- *     sd_advance : n <- n + advance, finished chains leave the batch                 ("Set n <- k")
+ *     sd_advance : n <- n + advance, finished chains leave the batch             (end of the loop body)
  *     sd_langevin_window : the whole window for unadjusted Langevin on a Gaussian-mixture energy,
  *                  fused in one launch (Sec. 5 and App. on Langevin diffusions)
  *
@@ -123,7 +123,7 @@ int sd_set_start_prediction(sd_ctx* ctx, const float* D_start);
 size_t sd_workspace_bytes(const sd_ctx* ctx, int32_t Bmax);
 int sd_set_workspace(sd_ctx* ctx, void* workspace /*dev*/, size_t bytes);
 
-/* Y_0 ~ N(0, Id), n = 0 ("Sample Y_0 ~ N(0, Id) and set n = 0").
+/* The chains' start: Y_0 ~ N(0, Id), n = 0 (first line of Alg. "Speculative Sampling for DDM").
  * chain_id [B] dev (in), y [B,d] dev (out), n [B] dev (out). */
 int sd_init_state(sd_ctx* ctx, int32_t B, const int64_t* chain_id, float* y, int32_t* n,
                   void* stream);
@@ -174,7 +174,8 @@ int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const in
               int32_t* adv, uint8_t* rejected, float* logratio, float* logu, void* stream);
 
 /* n += adv; a chain with n = T is finished: its state goes to out[chain_id] and it leaves the
- * batch; the others are packed to the front in their old order ("Set n <- k", while n < K).
+ * batch; the others are packed to the front in their old order (last line of the while-loop body of
+ * Alg. "Speculative Sampling for DDM" and the loop's condition).
  * in : y_out [B,d], adv [B], rejected [B] or NULL (only used for the counters)          (dev)
  * in place: y [B,d], n [B], chain_id [B] -- rewritten with the remaining chains        (dev)
  * out: out [*, d], row index = chain_id (caller sizes it); B_active: dev int32, number of

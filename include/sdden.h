@@ -11,8 +11,8 @@
  *   mlp      3-layer SiLU MLP on [x ; sinusoidal(k)], bf16 weights, fp32 accumulation (bf16 MFMA)
  *
  * Conventions as in sd.h: "dev" pointers are caller-owned device memory, "host" pointers are read
- * during the create call only.  Rows with krow < 0 are skipped: nothing is computed for them and
- * their output row is left untouched.  `alpha_bar_state` (host, length T+1) is the signal level of
+ * during the create call only.  Rows with krow < 0 or krow >= T are skipped: nothing is computed
+ * for them and their output row is left untouched.  `alpha_bar_state` (host, length T+1) is the signal level of
  * chain state k: x = sqrt(ab) x0 + sqrt(1-ab) eps.  sdden_eval only enqueues kernels on `stream`.
  */
 #ifndef SDDEN_H
@@ -51,7 +51,7 @@ int sdden_mlp_create(int32_t d, int32_t H, int32_t E, const uint16_t* W1, const 
  * larger Rmax (not while evaluations are in flight). */
 int sdden_reserve(sdden* den, int32_t Rmax);
 
-/* out[r] = D(X[r], krow[r]) for every r < R with krow[r] >= 0.
+/* out[r] = D(X[r], krow[r]) for every r < R with 0 <= krow[r] < T.
  * X [R,d], krow [R], out [R,d]: dev, 16-byte aligned; X and out must not overlap.
  * Enqueues kernels on `stream` only: no allocation, no synchronisation. */
 int sdden_eval(sdden* den, int32_t R, const float* X, const int32_t* krow, float* out,

@@ -1,8 +1,8 @@
 """ORACLE (test infrastructure only) -- the target network's prediction D(y, k), in fp64.
 
-The paper treats the drift b^q as a black-box network ("In practice, b_t is approximated using a
-neural network", Sec. 3.1).  The synthetic workloads replace it by functions with a plain
-definition, each written out here as that definition:
+The paper treats the drift b^q as a black box that a neural network stands in for (Sec. 3.1).  The
+synthetic workloads replace it by functions with a plain definition, each written out here as that
+definition:
 
 * ``GMMDenoiser``        E[x0 | x_t] for x0 ~ sum_m w_m N(mu_m, diag(s_m^2)), x_t = sqrt(ab) x0 +
                           sqrt(1-ab) eps -- Bayes' rule over the components.

@@ -97,5 +97,5 @@ def uniforms(seed: int, chain_id, k) -> np.ndarray:
 
 
 def initial_state(seed: int, chain_id, d: int) -> np.ndarray:
-    """Y_0 ~ N(0, Id) ("Sample Y_0 ~ N(0, Id) and set n = 0")."""
+    """The chain's start: Y_0 ~ N(0, Id), step index 0 (first line of Alg. "Speculative Sampling for DDM")."""
     return normals(seed, chain_id, np.zeros_like(np.asarray(chain_id)), d, STREAM_INIT)

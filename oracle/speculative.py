@@ -9,7 +9,8 @@ A plain, slow CPU statement of what the library's hot path computes, written fro
                             independent draft).
 * ``verify``                the accept / first-reject / reflect loop of the detailed algorithm
                             (App. "Detailed implementation of speculative sampling").
-* ``advance``               "Set n <- k" plus the batch bookkeeping the paper leaves implicit.
+* ``advance``               the step index moves to where the window stopped (last line of the while-loop
+                            body), plus the batch bookkeeping the paper leaves implicit.
 * ``window`` / ``sample``   one pass of the while-loop body of Alg. "Speculative Sampling for
                             DDM", and the whole loop.
 * ``sequential_chain``      the plain (non-speculative) target chain, eq. for q(y_k | y_{k-1}).
@@ -212,7 +213,7 @@ def verify(sched, y, n, chain_id, Ytil, Dq, K: int, seed: int, *, D0=None, mp=No
 
 
 # --------------------------------------------------------------------------------------
-# Bookkeeping: "Set n <- k", finished chains leave the batch
+# Bookkeeping: the step index moves to where the window stopped; finished chains leave the batch
 # --------------------------------------------------------------------------------------
 def advance(T: int, y_out, adv, n, chain_id, out):
     """n += adv; chains that reached T write their state to out[chain_id] and leave; the others
@@ -228,8 +229,9 @@ def advance(T: int, y_out, adv, n, chain_id, out):
 # One window and the whole sampler
 # --------------------------------------------------------------------------------------
 def target_predictions(sched, D: Denoiser, Ytil, krow, D0) -> np.ndarray:
-    """"In parallel, compute m^q_n(y~_n), ..., m^q_{n_L-1}(y~_{n_L-1})": Dq [B,K,d], row 0 = D0,
-    row j = D(Ytil[:, j-1], krow[:, j-1]) where krow >= 0."""
+    """The target's predictions at the window start and at every drafted state but the last, all of which
+    the algorithm obtains in one parallel evaluation (Alg. "Speculative Sampling for DDM", the parallel
+    step): Dq [B,K,d], row 0 = D0, row j = D(Ytil[:, j-1], krow[:, j-1]) where krow >= 0."""
     B, K, d = Ytil.shape
     Dq = np.zeros((B, K, d))
     Dq[:, 0] = D0

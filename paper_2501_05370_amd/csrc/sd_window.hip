@@ -158,7 +158,7 @@ __global__ __launch_bounds__(kBlock) void draft_frozen_kernel(DraftArgs p) {
         if (i0 + e < p.d) dst[e] = prev[e];
     }
     if (p.mirror) store_mirror<VEC>(p.mirror + static_cast<int64_t>(b) * p.rs * p.d + i0, prev, i0, p.d);
-    if (blk == 0) p.krow[static_cast<int64_t>(b) * p.rs] = n;
+    if (blk == 0) p.krow[static_cast<int64_t>(b) * p.rs] = n < p.T ? n : -1;   // a finished chain asks for no prediction
   }
   for (int j = 0; j < p.K; ++j) {       // position j+1 of the window, produces state n+j+1
     float out[4] = {0.f, 0.f, 0.f, 0.f};

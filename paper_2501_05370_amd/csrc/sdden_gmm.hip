@@ -40,7 +40,7 @@ struct GmmArgs {
   const float* ab;           // [T+1]
   const int32_t* active;
   int rows_per_chain;
-  int R, d, M;
+  int R, d, M, T;
 };
 
 // 1/v for v in [~1e-3, ~1e3]: the hardware fp32 reciprocal (1 ulp; the correctly rounded one is a
@@ -66,7 +66,8 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_kernel(
   const int r = blockIdx.x * kRowsPerBlock + wave;
   const int Ract = sdi::active_rows(p.active, p.rows_per_chain, p.R);
   const int k = r < Ract ? p.krow[r] : -1;
-  if (k < 0) return;                        // whole wavefront leaves together; no barriers used
+  // masked row (k < 0) or a step the chain does not have; the whole wavefront leaves together, no barriers used
+  if (static_cast<unsigned>(k) >= static_cast<unsigned>(p.T)) return;
   const double ab = p.ab[k];
   const double sab = sqrt(ab), om = 1.0 - ab;
   const float* x = p.X + static_cast<int64_t>(r) * p.d;
@@ -176,7 +177,8 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void gmm_posterior_mean_reg_ker
   const int r = blockIdx.x * kRowsPerBlock + wave;
   const int Ract = sdi::active_rows(p.active, p.rows_per_chain, p.R);
   const int k = r < Ract ? p.krow[r] : -1;
-  if (k < 0) return;                        // whole wavefront leaves together
+  // masked row (k < 0) or a step the chain does not have; the whole wavefront leaves together
+  if (static_cast<unsigned>(k) >= static_cast<unsigned>(p.T)) return;
   const double ab = p.ab[k];
   const double sab = sqrt(ab), om = 1.0 - ab;
   const int part = lane % PARTS, m = lane / PARTS;
@@ -253,7 +255,7 @@ struct GmmDenoiser final : sdden {
     p.Mp = Mp;
     p.lane_tab = lane_tab;
     p.cst = dev_cst; p.active = active; p.rows_per_chain = rows_per_chain;
-    p.R = R; p.d = d; p.M = M;
+    p.R = R; p.d = d; p.M = M; p.T = T;
     const size_t shmem = sizeof(double) * kRowsPerBlock * static_cast<size_t>(M + d);
     const unsigned grid = static_cast<unsigned>((R + kRowsPerBlock - 1) / kRowsPerBlock);
     prof.mark(1, st);

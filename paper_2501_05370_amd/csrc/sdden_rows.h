@@ -15,14 +15,15 @@ constexpr int kScan = 1024;
 
 constexpr int kScanBatch = 8;      // chunks of kScan rows whose steps are requested together
 
-// rowidx[0..count) = indices r < Ract with krow[r] >= 0, in increasing order; *count = how many.
+// rowidx[0..count) = indices r < Ract with 0 <= krow[r] < T, in increasing order; *count = how many (a step
+// index the chain does not have is a masked row like a negative one: the per-step tables end at T).
 // One workgroup walks the rows; it is a chain of global-load round trips unless the loads are batched, so a
 // thread requests its rows of kScanBatch chunks at once and the chunks are then ranked from registers.
 static __global__ __launch_bounds__(kScan) void compact_rows_kernel(const int32_t* __restrict__ krow,
                                                                     int32_t* __restrict__ rowidx,
                                                                     int32_t* __restrict__ count,
                                                                     const int32_t* active,
-                                                                    int rows_per_chain, int R) {
+                                                                    int rows_per_chain, int R, int T) {
   constexpr int NW = kScan / 64;
   __shared__ int wave_tot[kScanBatch][NW];
   const int Ract = sdi::active_rows(active, rows_per_chain, R);
@@ -33,7 +34,7 @@ static __global__ __launch_bounds__(kScan) void compact_rows_kernel(const int32_
 #pragma unroll
     for (int c = 0; c < kScanBatch; ++c) {
       const int r = start + c * kScan + tid;
-      keep[c] = r < Ract && krow[r] >= 0;
+      keep[c] = r < Ract && static_cast<unsigned>(krow[r]) < static_cast<unsigned>(T);
     }
     unsigned long long m[kScanBatch];
 #pragma unroll

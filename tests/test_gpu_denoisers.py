@@ -190,3 +190,45 @@ def test_c4_shaped_efficient_frozen_window_uses_the_bf16_image():
     adv = host(b.adv)
     Kt = np.minimum(K, T - n)
     assert np.all(adv >= 1) and np.all(adv <= Kt)
+
+
+def test_step_indices_the_chain_does_not_have_are_masked_rows():
+    """A step index >= T is treated like a negative one by every denoiser (their per-step tables end at T): the row
+    is skipped and its output left untouched; and the draft kernel of the efficient frozen drafter asks for no
+    prediction for a chain that is handed over at step T."""
+    from paper_2501_05370_amd.binding import Denoiser, SD_DRAFT_FROZEN_REUSED
+    rng = np.random.default_rng(3)
+    T, R = 12, 70
+    cases = []
+    p = W.lowrank_gaussian(rng, 64, 8)
+    sched = W.cosine_schedule(T)
+    g = Denoiser.sdden_lowrank_create(p.mu, p.U, p.s2, sched.alpha_bar_state)
+    g.sdden_reserve(R)
+    cases.append((g, 64))
+    pm = W.random_mlp(rng, 256, 256, 8)
+    cases.append((Denoiser.sdden_mlp_create(pm, T, R), 256))
+    cfg = W.make_config("c2", B=8, d=40, M=3, T=T)
+    cases.append((Denoiser.sdden_gmm_create(cfg.params.means, cfg.params.stds, cfg.params.logw, cfg.schedule.alpha_bar_state), 40))
+    for g, d in cases:
+        x = as_f32_f64(rng.standard_normal((R, d)))
+        k = rng.integers(0, T, size=R).astype(np.int32)
+        bad = np.array([3, 17, 40, 69])
+        k_bad = k.copy()
+        k_bad[bad] = [T, T + 3, 2 ** 30, -5]
+        out = torch.full((R, d), 777.0, dtype=torch.float32, device="cuda")
+        g.sdden_eval(R, f32(x), dev(k_bad, torch.int32), out)
+        ref = torch.full((R, d), 777.0, dtype=torch.float32, device="cuda")
+        g.sdden_eval(R, f32(x), dev(k, torch.int32), ref)
+        got, want = host(out), host(ref)
+        ok = np.ones(R, dtype=bool); ok[bad] = False
+        assert np.all(got[bad] == 777.0)
+        assert np.array_equal(got[ok], want[ok])
+    # sd_draft with one extra row per chain: row 0 carries the chain's own step, or -1 when the chain is at T
+    K, d, B = 4, 8, 3
+    ctx = make_context(W.linear_beta_schedule(T), d, K, seed=1, mode=SD_DRAFT_FROZEN_REUSED)
+    n = np.array([0, T - 1, T], dtype=np.int32)
+    X = torch.zeros(B, K + 1, d, dtype=torch.float32, device="cuda")
+    kr = torch.full((B, K + 1), 99, dtype=torch.int32, device="cuda")
+    ctx.sd_draft(B, f32(rng.standard_normal((B, d))), dev(n, torch.int32), dev(np.arange(B), torch.int64),
+                 f32(rng.standard_normal((B, d))), X, kr)
+    assert host(kr).tolist() == [[0, 1, 2, 3, 4], [T - 1, -1, -1, -1, -1], [-1, -1, -1, -1, -1]]

@@ -16,7 +16,8 @@ from oracle import langevin as L
 from oracle import speculative as S
 from oracle.denoisers import GMMDenoiser, GMMScore, LowRankDenoiser, MLPDenoiser
 
-from _gpu import as_f32_f64, decisions_match, dev, f32, host, rel_err
+from _gpu import (as_f32_f64, check_advance_on_matching_chains, decisions_match, dev, explain_divergent_chains, f32,
+                  gpu_chain_stepper, host, rel_err, ula_oracle_stepper)
 
 pytestmark = pytest.mark.gpu
 
@@ -30,17 +31,24 @@ def _states(cfg, rng, scale):
     return y, n.astype(np.int64)
 
 
-def _run_gpu_window(cfg, y, n, ids):
+def _run_gpu_window(cfg, y, n, ids, diagnostics=False):
     from paper_2501_05370_amd.runner import make_sampler
     smp = make_sampler(cfg)
     b = smp.buf
     b.y.copy_(torch.from_numpy(y)); b.n.copy_(dev(n, torch.int32)); b.chain_id.copy_(dev(ids, torch.int64))
-    smp.window(cfg.B)
+    smp.lr = smp.lu = None
+    if diagnostics:
+        smp.lr = torch.zeros(cfg.B, cfg.K, device="cuda"); smp.lu = torch.zeros(cfg.B, cfg.K, device="cuda")
+        smp.window(cfg.B, (smp.lr, smp.lu))
+    else:
+        smp.window(cfg.B)
     torch.cuda.synchronize()
     return smp
 
 
 def _compare_window(cfg, D, smp, y, n, ids, sample, tol, band, check_decisions=True):
+    """band None: the tie band of the decision comparison is derived from this very run -- four times the largest
+    difference between the GPU's and the oracle's log-ratio over the sampled chains (printed), at least 1e-6."""
     b = smp.buf
     sel = torch.as_tensor(sample, device="cuda")
     ys = y[sample].astype(np.float64)
@@ -54,15 +62,53 @@ def _compare_window(cfg, D, smp, y, n, ids, sample, tol, band, check_decisions=T
     adv = host(b.adv[sel])
     Kt = np.minimum(K, cfg.T - n[sample])
     assert np.all(adv >= np.minimum(2, Kt)) and np.all(adv <= Kt)
+    dl = None
+    if smp.lr is not None:
+        inwin = np.arange(K)[None, :] < Kt[:, None]
+        dl = float(np.max(np.abs(host(smp.lr[sel])[inwin] - res.logratio[inwin])))
+        assert np.max(np.abs(host(smp.lu[sel])[inwin] - res.logu[inwin])) < 1e-5
+    if band is None:
+        band = max(1e-6, 4.0 * dl)
     nbad, near = decisions_match(adv, res, band=band)
     same = adv == res.adv
     print(f"[{cfg.name} full size] sampled {len(sample)} of {cfg.B} chains: oracle mean adv {res.adv.mean():.2f}, "
-          f"rejected {res.rejected.mean():.2f}, decision mismatches {nbad} (near ties {near})")
+          f"rejected {res.rejected.mean():.2f}, decision mismatches {nbad} (near ties {near} in a band of {band:.1e}"
+          + (f"; largest |log-ratio GPU - oracle| {dl:.2e})" if dl is not None else ")"))
     if check_decisions:
         assert nbad == near
     assert same.mean() > 0.5
     assert rel_err(host(b.y_out[sel])[same], res.y_out[same]) < 5 * tol
     return res
+
+
+def _verify_on_oracle_inputs(cfg, D, smp, y, n, ids, sample, tol):
+    """Decision parity at the 1e-6 band of the contract, at full size: the oracle builds the verify inputs of the
+    sampled chains (its own predictions, rounded to fp32), their rows in the GPU's window tensors are overwritten
+    with them, and sd_verify runs on the FULL batch.  (The GPU's own window tensors are never oracle input.)"""
+    b = smp.buf
+    ys = y[sample].astype(np.float64)
+    D0 = as_f32_f64(D(ys, n[sample]))
+    Ytil, krow = S.draft_frozen(cfg.schedule, ys, n[sample], ids[sample], D0, cfg.K, cfg.seed)
+    Ytil = as_f32_f64(Ytil)
+    Dq = as_f32_f64(S.target_predictions(cfg.schedule, D, Ytil, krow, D0))
+    res = S.verify(cfg.schedule, ys, n[sample], ids[sample], Ytil, Dq, cfg.K, cfg.seed, D0=D0)
+    sel = torch.as_tensor(sample, device="cuda")
+    b.D0[sel] = f32(D0); b.Ytilde[sel] = f32(Ytil); b.Dq[sel] = f32(Dq)
+    outs = []
+    for diag in (True, False):                      # with the per-position diagnostics, and in the form the sampler runs
+        lr = torch.zeros(cfg.B, cfg.K, device="cuda"); lu = torch.zeros(cfg.B, cfg.K, device="cuda")
+        smp.ctx.sd_verify(cfg.B, b.y, b.n, b.chain_id, b.D0, b.Dq, b.Ytilde, b.y_out, b.adv, b.rejected,
+                          lr if diag else None, lu if diag else None)
+        outs.append((host(b.adv[sel]).copy(), host(b.y_out[sel]).copy(), host(lr[sel]).copy()))
+    adv = outs[0][0]
+    nbad, near = decisions_match(adv, res)
+    print(f"[{cfg.name} full size verify on the oracle's inputs] {len(sample)} chains, oracle mean adv {res.adv.mean():.2f}, "
+          f"rejected {res.rejected.mean():.2f}, mismatches {nbad} (near ties {near} at 1e-6)")
+    assert nbad == near
+    same = adv == res.adv
+    assert rel_err(outs[0][1][same], res.y_out[same]) < tol
+    assert np.max(np.abs(outs[0][2] - res.logratio) / np.maximum(1.0, np.abs(res.logratio))) < 1e-5
+    assert np.array_equal(outs[1][0], adv) and np.array_equal(outs[1][1], outs[0][1])
 
 
 def test_c2_full_size_all_chains():
@@ -75,14 +121,8 @@ def test_c2_full_size_all_chains():
     _compare_window(cfg, D, smp, y, n, ids, np.arange(cfg.B), 1e-5, 1e-6)
     # and the bookkeeping of the whole batch
     res, *_ = S.window(cfg.schedule, D, y.astype(np.float64), n, ids, cfg.K, seed=cfg.seed)
-    if np.array_equal(host(smp.buf.adv), res.adv):
-        out_ref = np.zeros((cfg.B, cfg.d))
-        y_ref, n_ref, id_ref = S.advance(cfg.T, res.y_out, res.adv, n, ids, out_ref)
-        smp.advance(cfg.B)
-        Ba = int(host(smp.buf.B_active)[0])
-        assert Ba == n_ref.size
-        assert np.array_equal(host(smp.buf.n)[:Ba], n_ref) and np.array_equal(host(smp.buf.chain_id)[:Ba], id_ref)
-        assert rel_err(host(smp.buf.y)[:Ba], y_ref) < 5e-5
+    checked = check_advance_on_matching_chains(smp, cfg.T, n, ids, res, host(smp.buf.adv).copy(), 5e-5)
+    assert checked >= cfg.B - 2
 
 
 def test_c3_full_size_sampled_chains():
@@ -90,11 +130,14 @@ def test_c3_full_size_sampled_chains():
     rng = np.random.default_rng(30)
     y, n = _states(cfg, rng, 1.0)
     ids = np.arange(cfg.B, dtype=np.int64)
-    smp = _run_gpu_window(cfg, y, n, ids)
+    smp = _run_gpu_window(cfg, y, n, ids, diagnostics=True)
     sample = np.concatenate([np.arange(8), rng.choice(np.arange(16, cfg.B), 88, replace=False)])
     D = LowRankDenoiser(cfg.params, cfg.schedule.alpha_bar_state)
-    # predictions differ by the fp32 rounding of two GEMMs over d = 3072: |delta log-ratio| stays below 1e-3
-    _compare_window(cfg, D, smp, y, n, ids, sample, 1e-5, 1e-3)
+    # end to end the predictions differ by the fp32 rounding of two GEMMs over d = 3072, which moves the log-ratio:
+    # the tie band of this comparison is four times the largest shift measured in this run (printed) ...
+    _compare_window(cfg, D, smp, y, n, ids, sample, 1e-5, None)
+    # ... and the decisions are held to the contract's 1e-6 on identical inputs
+    _verify_on_oracle_inputs(cfg, D, smp, y, n, ids, sample, 1e-5)
 
 
 def test_c4_full_size_sampled_chains():
@@ -103,31 +146,11 @@ def test_c4_full_size_sampled_chains():
     y, n = _states(cfg, rng, 1.0)
     ids = np.arange(cfg.B, dtype=np.int64)
     smp = _run_gpu_window(cfg, y, n, ids)
-    sample = np.array([0, 3, 17, 200, 511])
+    sample = np.unique(np.concatenate([[0, 3, 17, 511], rng.choice(np.arange(18, 500), 30, replace=False)]))   # 34 chains
     D = MLPDenoiser(cfg.params)
     # bf16 predictions move the log-ratio by O(0.1): decisions are compared on identical inputs below
     _compare_window(cfg, D, smp, y, n, ids, sample, 2e-2, 1e-6, check_decisions=False)
-    # verify at full size on the GPU's own window tensors is not allowed as oracle input; instead
-    # the oracle builds the verify inputs of the sampled chains and the GPU verifies the FULL
-    # batch in which those chains' rows are overwritten with the oracle's
-    b = smp.buf
-    ys = y[sample].astype(np.float64)
-    D0 = as_f32_f64(D(ys, n[sample]))
-    Ytil, krow = S.draft_frozen(cfg.schedule, ys, n[sample], ids[sample], D0, cfg.K, cfg.seed)
-    Ytil = as_f32_f64(Ytil)
-    Dq = as_f32_f64(S.target_predictions(cfg.schedule, D, Ytil, krow, D0))
-    res = S.verify(cfg.schedule, ys, n[sample], ids[sample], Ytil, Dq, cfg.K, cfg.seed, D0=D0)
-    sel = torch.as_tensor(sample, device="cuda")
-    b.D0[sel] = f32(D0); b.Ytilde[sel] = f32(Ytil); b.Dq[sel] = f32(Dq)
-    lr = torch.zeros(cfg.B, cfg.K, device="cuda"); lu = torch.zeros(cfg.B, cfg.K, device="cuda")
-    smp.ctx.sd_verify(cfg.B, b.y, b.n, b.chain_id, b.D0, b.Dq, b.Ytilde, b.y_out, b.adv, b.rejected, lr, lu)
-    adv = host(b.adv[sel])
-    nbad, near = decisions_match(adv, res)
-    print(f"[c4 full size verify] oracle adv {res.adv.tolist()}, gpu adv {adv.tolist()}, mismatches {nbad} (near ties {near})")
-    assert nbad == near
-    same = adv == res.adv
-    assert rel_err(host(b.y_out[sel])[same], res.y_out[same]) < 1e-5
-    assert np.max(np.abs(host(lr[sel]) - res.logratio) / np.maximum(1.0, np.abs(res.logratio))) < 1e-5
+    _verify_on_oracle_inputs(cfg, D, smp, y, n, ids, sample, 1e-5)
 
 
 def test_c5_full_size_sampled_chains():
@@ -237,4 +260,5 @@ def test_langevin_full_size_run_equals_the_window_loop(name, T):
     diverged = int((err > 1e-3).sum())
     print(f"[{name} one launch, {B} chains, T={T}] counters {cf}; {len(sample)} chains against the oracle: "
           f"max err {err.max():.2e}, off-path {diverged}")
-    assert diverged <= 2
+    assert explain_divergent_chains(err, sample, *gpu_chain_stepper(cfg), *ula_oracle_stepper(grad, cfg, cfg.seed), T,
+                                    f"{name} one launch") == diverged

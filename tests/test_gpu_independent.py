@@ -131,7 +131,16 @@ def test_independent_free_running_sampler_lowrank():
     print(f"[independent lowrank run] GPU counters {counters}, oracle steps {st.steps} chain-windows {st.chain_windows} "
           f"rejections {st.rejections}, mean advance {st.mean_advance:.2f}; chains off the oracle path: {diverged}")
     assert counters[0] == cfg.B * cfg.T
-    assert diverged <= 3
+    from _gpu import explain_divergent_chains, gpu_chain_stepper
+    from oracle import philox
+
+    def ostep(state, n, cid):
+        r, *_ = S.window(cfg.schedule, D, state[0][None], np.array([n]), np.array([cid], dtype=np.int64), cfg.K, seed=cfg.seed,
+                         drafter="independent", D_draft=Dd)
+        return (r.y_out[0],), int(r.adv[0]), r.logratio[0], r.logu[0]
+    ostart = lambda cid: (philox.initial_state(cfg.seed, np.array([cid], dtype=np.int64), cfg.d)[0],)
+    assert explain_divergent_chains(err, np.arange(cfg.B), *gpu_chain_stepper(cfg, drafter="independent", draft_params=dp),
+                                    ostart, ostep, cfg.T, "independent lowrank run") == diverged
     if diverged == 0:
         assert counters[1] == st.chain_windows and counters[2] == st.rejections
     assert np.max(err[err <= 1e-3]) < 1e-4

@@ -10,7 +10,7 @@ from oracle import langevin as L
 from oracle import speculative as S
 from oracle.denoisers import GMMDenoiser, GMMScore
 
-from _gpu import as_f32_f64, decisions_match, dev, f32, host, make_context, rel_err
+from _gpu import explain_divergent_chains, gpu_chain_stepper, ula_oracle_stepper, as_f32_f64, decisions_match, dev, f32, host, make_context, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -61,7 +61,14 @@ def test_c1_window_by_window_and_free_running():
     print(f"[c1 free run] GPU counters {counters}, oracle steps {st.steps} windows {st.chain_windows} "
           f"rejections {st.rejections}; chains off the oracle path: {diverged}")
     assert counters[0] == B * T
-    assert diverged <= 2                                   # a flipped near-tie moves a whole chain
+    # a flipped near-tie moves a whole chain: every chain that ends off the oracle's path must part from it at one
+    gstart, gstep = gpu_chain_stepper(cfg)
+
+    def ostep(state, n, cid):
+        r, *_ = S.window(cfg.schedule, den, state[0][None], np.array([n]), np.array([cid], dtype=np.int64), K, seed=cfg.seed)
+        return (r.y_out[0],), int(r.adv[0]), r.logratio[0], r.logu[0]
+    ostart = lambda cid: (philox.initial_state(cfg.seed, np.array([cid], dtype=np.int64), d)[0],)
+    assert explain_divergent_chains(err, np.arange(B), gstart, gstep, ostart, ostep, T, "c1 free run") == diverged
     if diverged == 0:
         assert counters[1] == st.chain_windows and counters[2] == st.rejections
 
@@ -141,7 +148,9 @@ def test_langevin_free_run_small():
     err = np.max(np.abs(host(out) - ref), axis=1) / np.maximum(1.0, np.abs(ref).max(axis=1))
     diverged = int((err > 1e-3).sum())
     print(f"[langevin free run] counters {counters}, oracle chain-windows {cw} rejections {rejections}, off-path {diverged}")
-    assert counters[0] == cfg.B * cfg.T and diverged <= 1
+    assert counters[0] == cfg.B * cfg.T
+    assert explain_divergent_chains(err, np.arange(cfg.B), *gpu_chain_stepper(cfg, seed=5),
+                                    *ula_oracle_stepper(GMMScore(p), cfg, 5), cfg.T, "langevin free run") == diverged
     if diverged == 0:
         assert counters[1] == cw and counters[2] == rejections
 
@@ -203,7 +212,10 @@ def test_phi4_langevin_free_run_and_argument_checks():
     err = np.max(np.abs(host(out) - ref), axis=1) / np.maximum(1.0, np.abs(ref).max(axis=1))
     diverged = int((err > 1e-3).sum())
     print(f"[phi4 free run] counters {counters}, oracle chain-windows {cw} rejections {rejections}, off-path {diverged}")
-    assert counters[0] == cfg.B * cfg.T and diverged <= 2
+    assert counters[0] == cfg.B * cfg.T
+    assert explain_divergent_chains(err, np.arange(cfg.B), *gpu_chain_stepper(cfg),
+                                    *ula_oracle_stepper(Phi4Energy(cfg.params.L, cfg.params.beta), cfg, cfg.seed), cfg.T,
+                                    "phi4 free run") == diverged
     if diverged == 0:
         assert counters[1] == cw and counters[2] == rejections
     b = smp.buf
@@ -236,7 +248,9 @@ def test_langevin_run_equals_the_window_loop_and_the_oracle(B, d, M, K, T):
     err = np.max(np.abs(xf - ref), axis=1) / np.maximum(1.0, np.abs(ref).max(axis=1))
     diverged = int((err > 1e-3).sum())
     print(f"[langevin run d={d}] counters {cf}, oracle chain-windows {ocw} rejections {orej}, off-path {diverged}")
-    assert cf[0] == B * T and diverged <= 1
+    assert cf[0] == B * T
+    assert explain_divergent_chains(err, np.arange(B), *gpu_chain_stepper(cfg, seed=5),
+                                    *ula_oracle_stepper(GMMScore(p), cfg, 5), T, f"langevin run d={d}") == diverged
     if diverged == 0:
         assert cf[1] == ocw and cf[2] == orej
     # a bound on the windows per chain: two windows advance a chain by 2..2K steps, and a second call finishes
