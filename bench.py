@@ -109,7 +109,7 @@ def _sampler(cfg, drafter):
     return make_sampler(cfg, drafter=drafter)
 
 
-def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1, verify_shape=0):
+def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1, verify_shape=0, gemm_variant=0):
     import torch
     from paper_2501_05370_amd.runner import make_sampler
     from paper_2501_05370_amd.sampler import StageTimer
@@ -120,6 +120,8 @@ def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1, v
     smp = _sampler(cfg, drafter)
     if verify_shape:
         smp.ctx.sd_set_verify_shape(verify_shape)
+    if gemm_variant:
+        smp.den.sdden_mlp_select_gemm(gemm_variant)
     ids = torch.arange(cfg.B, dtype=torch.int64, device="cuda")
     plan = roofline_plan(cfg)
     run_kw = {} if loop in ("eager", "fused") else dict(windows_per_sync=wps, graph=(loop == "graph"))
@@ -184,6 +186,20 @@ def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1, v
                 "work_per_launch": work / max(1, k_launches)}
     if timed_note:
         roofline["timed_in"] = timed_note
+    if cfg.kind == "langevin":
+        # The algorithmic count prices the weighted mean over all M components (2 M d of the 5 M d); the kernel skips
+        # components whose responsibility is below 1e-25, which changes nothing to fp64 rounding.  Live components
+        # are counted here on the final states of the run (this well-separated mixture leaves one or two).
+        M = cfg.params.means.shape[0]
+        x = smp.buf.y_out[:min(cfg.B, 2048)].double()
+        mu = torch.as_tensor(cfg.params.means, dtype=torch.float64, device=x.device)
+        s2 = float(cfg.params.stds[0, 0]) ** 2
+        logit = torch.as_tensor(cfg.params.logw, dtype=torch.float64, device=x.device)[None, :] - torch.cdist(x, mu) ** 2 / (2 * s2)
+        live = float((torch.softmax(logit, dim=1) > 1e-25).sum(dim=1).double().mean().item())
+        executed = (3.0 * M + 2.0 * live + 14.0) / (5.0 * M + 14.0)
+        roofline["executed"] = {"live_components_of_%d" % M: round(live, 2), "achieved": round(achieved * executed, 3),
+                                "frac": round(achieved * executed / peak, 5),
+                                "note": "flops the kernel executes: the weighted mean runs over the live components only"}
     stage_table = {k: {"ms_total": round(v[0], 3), "launches": v[1], "us_per_launch": round(1e3 * v[0] / max(1, v[1]), 2)}
                    for k, v in timed.items()} if stages else None
     return elapsed, counters, roofline, stage_table
@@ -241,70 +257,100 @@ def run_context(cfg, drafter="frozen"):
     return out
 
 
-def cpu_baseline(cfg, budget_s=15.0, drafter="frozen"):
-    """Time the oracle on a bounded sample of the workload: a subset of the chains, run window by
-    window until the time budget is used or the chains finish."""
+_ORACLE = {}          # what the oracle workers need, built once in the parent (forked workers share it copy-on-write)
+
+
+def _oracle_setup(cfg, drafter):
     import workloads as W
     from oracle import langevin as L
-    from oracle import philox
-    from oracle import speculative as S
     from oracle.denoisers import GMMDenoiser, GMMScore, LowRankDenoiser, MLPDenoiser
-    try:
-        from threadpoolctl import threadpool_info
-        blas_threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-    except Exception:
-        blas_threads = 1
-    nchains = {"c1": 64, "c2": 256, "c3": 16, "c4": 4, "c5": 16, "phi4": 256}[cfg.name]
-    nchains = min(nchains, cfg.B)
-    ids = np.arange(nchains, dtype=np.int64)
     sched = cfg.schedule
     if cfg.kind == "gmm":
-        D, cores = GMMDenoiser(cfg.params, sched.alpha_bar_state), 1
+        D = GMMDenoiser(cfg.params, sched.alpha_bar_state)
     elif cfg.kind == "lowrank":
-        D, cores = LowRankDenoiser(cfg.params, sched.alpha_bar_state), blas_threads
+        D = LowRankDenoiser(cfg.params, sched.alpha_bar_state)
     elif cfg.kind == "mlp":
-        D, cores = MLPDenoiser(cfg.params), blas_threads
+        D = MLPDenoiser(cfg.params)
     elif cfg.kind == "phi4":
-        D, cores = L.Phi4Energy(cfg.params.L, cfg.params.beta), 1
+        D = L.Phi4Energy(cfg.params.L, cfg.params.beta)
     else:
-        D, cores = GMMScore(cfg.params), 1
+        D = GMMScore(cfg.params)
     kw = {}
     if drafter == "independent":
         dp = W.draft_params(cfg)
         Dd = {"gmm": lambda: GMMDenoiser(dp, sched.alpha_bar_state), "lowrank": lambda: LowRankDenoiser(dp, sched.alpha_bar_state),
               "mlp": lambda: MLPDenoiser(dp)}[cfg.kind]()
         kw = dict(drafter="independent", D_draft=Dd)
-    ids0 = ids
-    out = np.zeros((nchains, cfg.d))
+    _ORACLE.update(cfg=cfg, D=D, kw=kw, drafter=drafter)
+
+
+def _oracle_share(job):
+    """The oracle on chains first .. first + nchains - 1 of the workload, window by window, for budget_s seconds of
+    wall time or until they finish (then again with the next seed).  One BLAS thread: the cores are used by running
+    several of these at once.  Returns (verified steps, windows, passes, seconds)."""
+    first, nchains, budget_s = job
+    from threadpoolctl import threadpool_limits
+    from oracle import langevin as L
+    from oracle import philox
+    from oracle import speculative as S
+    cfg, D, kw, drafter = _ORACLE["cfg"], _ORACLE["D"], _ORACLE["kw"], _ORACLE["drafter"]
+    sched = cfg.schedule
+    ids0 = np.arange(first, first + nchains, dtype=np.int64)
+    out = np.zeros((first + nchains, cfg.d))
     steps_done = windows = runs = 0
     seed = cfg.seed
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < budget_s:
+            # a fresh pass over the sampled chains (small workloads finish several within the budget)
+            ids = ids0
+            y = philox.initial_state(seed, ids, cfg.d)
+            n = np.zeros(nchains, dtype=np.int64)
+            runs += 1
+            Dfz = D(y, n) if drafter == "efficient_frozen" else None
+            while n.size and time.perf_counter() - t0 < budget_s:
+                if drafter == "efficient_frozen":
+                    res, _, _, _, Dnext = S.window_efficient(sched, D, y, n, ids, Dfz, cfg.K, seed)
+                    y_out, adv = res.y_out, res.adv
+                    Dfz = Dnext[n + adv < cfg.T]
+                elif cfg.kind in ("langevin", "phi4"):
+                    y_out, adv, _, _, _ = L.ula_window(D, y, n, ids, cfg.K, cfg.T, cfg.gamma, seed)
+                else:
+                    res, *_ = S.window(sched, D, y, n, ids, cfg.K, seed, **kw)
+                    y_out, adv = res.y_out, res.adv
+                steps_done += int(adv.sum())
+                windows += 1
+                y, n, ids = S.advance(cfg.T, y_out, adv, n, ids, out)
+            seed += 1
+        dt = time.perf_counter() - t0
+    return steps_done, windows, runs, dt
+
+
+def cpu_baseline(cfg, budget_s=10.0, drafter="frozen"):
+    """The oracle timed on the host on a bounded sample of the workload, twice: on one core, and with the chains
+    split over all the cores this process may use (one single-threaded worker process per core, at most 16).
+    Must run before anything initialises the GPU: the workers are forked."""
+    import multiprocessing as mp
+    nchains = {"c1": 64, "c2": 256, "c3": 16, "c4": 4, "c5": 16, "phi4": 256}[cfg.name]
+    nchains = min(nchains, cfg.B)
+    _oracle_setup(cfg, drafter)
+    s1, w1, r1, dt1 = _oracle_share((0, nchains, budget_s))
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))
+    per = max(1, min(nchains, cfg.B // cores))
+    jobs = [(c * per, per, budget_s) for c in range(cores)]
     t0 = time.perf_counter()
-    while time.perf_counter() - t0 < budget_s:
-        # a fresh pass over the sampled chains (small workloads finish several within the budget)
-        ids = ids0
-        y = philox.initial_state(seed, ids, cfg.d)
-        n = np.zeros(nchains, dtype=np.int64)
-        runs += 1
-        Dfz = D(y, n) if drafter == "efficient_frozen" else None
-        while n.size and time.perf_counter() - t0 < budget_s:
-            if drafter == "efficient_frozen":
-                res, _, _, _, Dnext = S.window_efficient(sched, D, y, n, ids, Dfz, cfg.K, seed)
-                y_out, adv = res.y_out, res.adv
-                Dfz = Dnext[n + adv < cfg.T]
-            elif cfg.kind in ("langevin", "phi4"):
-                y_out, adv, _, _, _ = L.ula_window(D, y, n, ids, cfg.K, cfg.T, cfg.gamma, seed)
-            else:
-                res, *_ = S.window(sched, D, y, n, ids, cfg.K, seed, **kw)
-                y_out, adv = res.y_out, res.adv
-            steps_done += int(adv.sum())
-            windows += 1
-            y, n, ids = S.advance(cfg.T, y_out, adv, n, ids, out)
-        seed += 1
-    dt = time.perf_counter() - t0
-    return {"value": round(steps_done / dt, 3), "unit": "verified diffusion steps/s", "cores": cores,
-            "kind": "oracle",
-            "sample": f"{nchains} of {cfg.B} chains, {windows} windows in {runs} pass(es) from step 0 "
-                      f"({steps_done} verified steps in {dt:.1f} s; numpy fp64)"}
+    with mp.get_context("fork").Pool(cores) as pool:
+        parts = pool.map(_oracle_share, jobs)
+    wall = time.perf_counter() - t0
+    sp = sum(q[0] for q in parts)
+    unit = "verified diffusion steps/s"
+    return {"value": round(sp / wall, 3), "unit": unit, "cores": cores, "kind": "oracle",
+            "sample": f"{cores} worker processes (one BLAS thread each) x {per} chains of {cfg.B}, "
+                      f"{sum(q[1] for q in parts)} windows from step 0 ({sp} verified steps in {wall:.1f} s of wall time, "
+                      f"process start-up included; numpy fp64)",
+            "one_core": {"value": round(s1 / dt1, 3), "unit": unit, "cores": 1,
+                         "sample": f"{nchains} of {cfg.B} chains, {w1} windows in {r1} pass(es) from step 0 "
+                                   f"({s1} verified steps in {dt1:.1f} s; numpy fp64, one thread)"}}
 
 
 def kernel_gemm(iters=20, rows_per_chain_masked=1, variants=None):
@@ -512,6 +558,8 @@ def main():
     ap.add_argument("--windows-per-sync", type=int, default=4)
     ap.add_argument("--verify-shape", type=int, default=0,
                     help="launch shape of the accept / reflect kernel in the sampler (sd_set_verify_shape; 0 = default)")
+    ap.add_argument("--gemm-variant", type=int, default=0,
+                    help="MLP GEMM kernel in the sampler (sdden_mlp_select_gemm; 0 = default; the workload must use the MLP)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the untimed extras (acceptance by position, sequential chain on the GPU)")
@@ -555,6 +603,9 @@ def main():
         raise SystemExit("bench.py: this build runs on ONE GPU only (chains are independent and would shard by "
                          "chain id with no collective on the hot path); run with --gpus 1")
     import workloads as W
+    import torch
+    if torch.cuda.device_count() < 1:          # counting devices does not initialise the GPU
+        raise SystemExit("bench.py needs a GPU (the HIP library has no CPU fallback)")
     cfg = W.make_config(args.workload)
     steps = args.steps if args.steps is not None else {"c1": 20, "c2": 10, "c3": 3, "c4": 3, "c5": 2, "phi4": 3}[cfg.name]
     if args.drafter != "frozen" and cfg.kind in ("langevin", "phi4"):
@@ -563,8 +614,10 @@ def main():
         raise SystemExit("bench.py: --loop fused is the one-launch form of the Langevin workloads (c5, phi4)")
     loop = args.loop or ({"c1": "graph", "c2": "multi", "c3": "multi", "c5": "fused", "phi4": "fused"}.get(cfg.name, "eager")
                          if args.drafter == "frozen" else "eager")
+    # the oracle is timed first: its worker processes are forked, which must not happen once the GPU is initialised
+    baseline = None if args.no_cpu_baseline else cpu_baseline(cfg, drafter=args.drafter)
     elapsed, counters, roofline, stage_table = run_gpu(cfg, steps, args.warmup, args.stages, args.drafter, loop,
-                                                       args.windows_per_sync, args.verify_shape)
+                                                       args.windows_per_sync, args.verify_shape, args.gemm_variant)
     total_steps = counters[0]
     assert total_steps == cfg.B * cfg.T * steps, (total_steps, cfg.B, cfg.T, steps)
     line = {
@@ -590,8 +643,8 @@ def main():
         line["stages"] = stage_table
     if not args.no_context:
         line["context"] = run_context(cfg, args.drafter)
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg, drafter=args.drafter)
+    if baseline is not None:
+        line["cpu_baseline"] = baseline
     print(json.dumps(line))
 
 

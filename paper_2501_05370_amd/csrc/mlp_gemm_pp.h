@@ -241,18 +241,18 @@ __global__ __launch_bounds__(512) void kernel_pp(Args p) {
   MLPPP_LD_SLICE(1, 64);
   MLPPP_VMWAIT(8);                                                 // slice 0 has landed, slice 1 may be in flight
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  u32x4 fa[8] = {}, bx[4], by[4] = {};
+  u32x4 fa[8] = {}, bx[4] = {}, by[4] = {};
+  int kt = 0;
   MLPPP_READ_B(bx, 0, 0);
   MLPPP_WAIT_B(bx);
   MLPPP_PHASE_END();                           // every wavefront holds its B0 of slice 0: that region may be refilled
   if (grp == 1) MLPPP_PHASE_END();             // group 1 starts one phase late
-  int kt = 0;
   for (; kt + 3 < nk; kt += 2) {
     MLPPP_SLICE(0, bx, by, kt + 2, 1, 1, 12, 12, 12, 12);
     MLPPP_SLICE(1, by, bx, kt + 3, 1, 1, 12, 12, 12, 12);
   }
-  MLPPP_SLICE(0, bx, by, 0, 0, 1, 10, 8, 6, 4);   // slice nk-2: nothing left to request
-  MLPPP_SLICE(1, by, bx, 0, 0, 0, 2, 0, 0, 0);    // slice nk-1
+  MLPPP_SLICE(0, bx, by, 0, 0, 1, 10, 8, 6, 4);     // slice nk-2: nothing left to request
+  MLPPP_SLICE(1, by, bx, 0, 0, 0, 2, 0, 0, 0);      // slice nk-1
   if (grp == 0) MLPPP_PHASE_END();             // group 0 waits for group 1's last phase: equal barrier counts
 #undef MLPPP_SLICE
 #undef MLPPP_COMPUTE
