@@ -252,7 +252,7 @@ struct LowRankDenoiser final : sdden {
     if (!sdi::aligned16(X)) return sdi::fail(err, SD_ERR_ARG, "sdden_eval(lowrank): X must be 16-byte aligned");
     if (R > cap_rows)
       return sdi::fail(err, SD_ERR_WORKSPACE, "sdden_eval(lowrank): %d rows exceed the %d reserved (sdden_reserve)", R, cap_rows);
-    hipLaunchKernelGGL(sdrows::compact_rows_kernel, dim3(1), dim3(sdrows::kScan), 0, st, krow, rowidx, count,
+    hipLaunchKernelGGL(sdrows::compact_rows_kernel, dim3(sdrows::compact_rows_grid(R)), dim3(sdrows::kScan), 0, st, krow, rowidx, count,
                        active, rows_per_chain, R, T);
     if (part) return eval_ring(R, X, krow, out, st);
     GemmArgs a;

@@ -151,7 +151,7 @@ struct MlpDenoiser final : sdden {
       return sdi::fail(err, SD_ERR_ARG, "sdden_eval(mlp): X and out must be 16-byte aligned");
     if (Xbf16 && !sdi::aligned16(Xbf16))
       return sdi::fail(err, SD_ERR_ARG, "sdden_eval_mirror(mlp): Xbf16 must be 16-byte aligned");
-    hipLaunchKernelGGL(sdrows::compact_rows_kernel, dim3(1), dim3(sdrows::kScan), 0, st, krow, rowidx, count,
+    hipLaunchKernelGGL(sdrows::compact_rows_kernel, dim3(sdrows::compact_rows_grid(R)), dim3(sdrows::kScan), 0, st, krow, rowidx, count,
                        active, rows_per_chain, R, T);
     mlpgemm::Args a;
     a.count = count; a.rowidx = rowidx; a.krow = krow; a.arow = nullptr;

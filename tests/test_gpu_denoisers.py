@@ -232,3 +232,32 @@ def test_step_indices_the_chain_does_not_have_are_masked_rows():
     ctx.sd_draft(B, f32(rng.standard_normal((B, d))), dev(n, torch.int32), dev(np.arange(B), torch.int64),
                  f32(rng.standard_normal((B, d))), X, kr)
     assert host(kr).tolist() == [[0, 1, 2, 3, 4], [T - 1, -1, -1, -1, -1], [-1, -1, -1, -1, -1]]
+
+
+@pytest.mark.parametrize("R,pattern", [(8192 * 2, "random"), (8192 * 3 + 517, "random"), (8192 * 2 + 1, "last_share_masked"),
+                                       (8193, "first_share_masked")])
+def test_row_compaction_over_several_workgroups(R, pattern):
+    """More rows than one workgroup of the row-compaction kernel ranks (8192): every workgroup has to place its
+    kept rows behind those of the shares before it.  Checked through the low-rank denoiser, whose output rows
+    must be the oracle's for every kept row and untouched for every masked one."""
+    from paper_2501_05370_amd.binding import Denoiser
+    d, r, T = 64, 8, 20
+    rng = np.random.default_rng(7)
+    p = W.lowrank_gaussian(rng, d, r)
+    sched = W.cosine_schedule(T)
+    den = LowRankDenoiser(p, sched.alpha_bar_state)
+    g = Denoiser.sdden_lowrank_create(p.mu, p.U, p.s2, sched.alpha_bar_state)
+    g.sdden_reserve(R)
+    x, k = _rows(rng, R, T, d, 1.3)
+    if pattern == "last_share_masked":
+        k[8192 * 2:] = -1
+    if pattern == "first_share_masked":
+        k[:8192] = -1
+    out = torch.full((R, d), 777.0, dtype=torch.float32, device="cuda")
+    g.sdden_eval(R, f32(x), dev(k, torch.int32), out)
+    got = host(out)
+    want = den(x[k >= 0], k[k >= 0])
+    err = rel_err(got[k >= 0], want)
+    print(f"[row compaction R={R} {pattern}] rows {int((k >= 0).sum())}/{R}, rel err {err:.2e}")
+    assert err < 1e-5
+    assert np.all(got[k < 0] == 777.0)
