@@ -307,14 +307,27 @@ def sample(sched, D: Denoiser, B: int, d: int, K: int, seed: int, *, drafter: st
 # draft strategy): the draft mean freezes the target's prediction at the DRAFT state of the
 # window's first position, D(y~_n, n), which the previous window's verification computed, instead
 # of a fresh D(y_n, n).  A window then needs one batched target call, on y_n and all Kt drafts.
+# The paragraph's last sentence names an alternative for the case y~_n != y_n (the previous window
+# ended with a rejection): freeze the prediction at the last ACCEPTED state, D(y_{n-1}, n-1), which
+# that call computed as well.  carry = "draft" is the first rule, "last_accepted" the second.
 # --------------------------------------------------------------------------------------
-def window_efficient(sched, D: Denoiser, y, n, chain_id, Dfz, K: int, seed: int, *, tau: float = 1.0):
+CARRY_RULES = ("draft", "last_accepted")
+
+
+def window_efficient(sched, D: Denoiser, y, n, chain_id, Dfz, K: int, seed: int, *, tau: float = 1.0,
+                     carry: str = "draft"):
     """One window with the carried-over frozen prediction ``Dfz`` [B,d].
 
     Returns (VerifyResult, Ytil, Dq_ext [B,K+1,d], krow_ext [B,K+1], Dfz_next [B,d]):
     Dq_ext[:, j] = D(state j of the window, n+j) for j = 0 (y_n itself) .. Kt (rows whose step
-    index would be T are not evaluated and stay zero), and Dfz_next = Dq_ext[b, adv[b]], the
-    prediction at the draft state of the position the next window starts from."""
+    index would be T are not evaluated and stay zero).  Dfz_next, the vector the next window
+    freezes: carry "draft": Dq_ext[b, adv[b]], the prediction at the draft state of the position
+    the next window starts from (the rejected draft, or the last accepted one when nothing was
+    rejected); carry "last_accepted": after a rejection Dq_ext[b, adv[b]-1] instead, the
+    prediction at the last state the chain kept unchanged (the window's own start state when the
+    first draft was rejected), at that state's step index."""
+    if carry not in CARRY_RULES:
+        raise ValueError(f"carry must be one of {CARRY_RULES}")
     y = np.asarray(y, dtype=np.float64)
     n = np.asarray(n)
     B, d = y.shape
@@ -340,12 +353,15 @@ def window_efficient(sched, D: Denoiser, y, n, chain_id, Dfz, K: int, seed: int,
     b_idx, j_idx = np.nonzero(krow_ext >= 0)
     Dq_ext[b_idx, j_idx] = D(X_ext[b_idx, j_idx], krow_ext[b_idx, j_idx])
     res = verify(sched, y, n, chain_id, Ytil, Dq_ext[:, :K], K, seed, mp=mp, tau=tau)
-    Dfz_next = Dq_ext[np.arange(B), res.adv]
+    row = res.adv.copy()
+    if carry == "last_accepted":
+        row = row - res.rejected.astype(row.dtype)
+    Dfz_next = Dq_ext[np.arange(B), row]
     return res, Ytil, Dq_ext, krow_ext, Dfz_next
 
 
 def sample_efficient(sched, D: Denoiser, B: int, d: int, K: int, seed: int, *, tau: float = 1.0,
-                     chain_ids: Optional[np.ndarray] = None):
+                     chain_ids: Optional[np.ndarray] = None, carry: str = "draft"):
     """The whole sampler with the efficient frozen drafter; initialised with D(y_0, 0).
     Returns (Y_T, stats): stats.target_calls = 1 + number of windows."""
     ids0 = np.arange(B, dtype=np.int64) if chain_ids is None else np.asarray(chain_ids, dtype=np.int64)
@@ -357,7 +373,7 @@ def sample_efficient(sched, D: Denoiser, B: int, d: int, K: int, seed: int, *, t
     Dfz = D(y, n)
     st.target_calls, st.target_rows = 1, n.size
     while n.size:
-        res, _, _, krow_ext, Dfz_next = window_efficient(sched, D, y, n, ids, Dfz, K, seed, tau=tau)
+        res, _, _, krow_ext, Dfz_next = window_efficient(sched, D, y, n, ids, Dfz, K, seed, tau=tau, carry=carry)
         st.windows += 1
         st.chain_windows += n.size
         st.steps += int(res.adv.sum())

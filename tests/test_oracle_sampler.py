@@ -6,6 +6,7 @@ degenerate draft == target case, the advance law under i.i.d. acceptance, and th
 marginals of an affine-Gaussian chain.
 """
 import numpy as np
+import pytest
 from scipy import stats
 
 import workloads as W
@@ -234,3 +235,49 @@ def test_efficient_frozen_sampler_is_exact_in_law():
     radius = lambda v: np.linalg.norm(v, axis=1)
     for f in (lambda v: v[:, 0], lambda v: v[:, 1], radius, lambda v: np.arctan2(v[:, 1], v[:, 0])):
         assert stats.ks_2samp(f(spec), f(seq)).pvalue > 1e-4
+
+
+def test_efficient_frozen_last_accepted_rule_structure():
+    """The alternative carry rule of the same appendix paragraph: after a rejection the next window freezes the
+    prediction at the last state the chain kept, with that state's step index.  Rebuilt here from the states
+    themselves (a direct call of the denoiser, not an index into the window's prediction array), so a wrong row or
+    a wrong step index fails; chains without a rejection carry the same vector under both rules."""
+    sched, den = _ring(T=12)
+    rng = np.random.default_rng(4)
+    B, K, d = 400, 4, 2
+    y = rng.standard_normal((B, d)) * 2
+    n = rng.integers(0, 12, size=B)
+    ids = np.arange(B, dtype=np.int64) + 9
+    stale = den(y, n) + 0.5 * rng.standard_normal((B, d))
+    res_a, Ytil_a, _, _, next_a = S.window_efficient(sched, den, y, n, ids, stale, K, seed=8, carry="draft")
+    res_b, Ytil_b, _, _, next_b = S.window_efficient(sched, den, y, n, ids, stale, K, seed=8, carry="last_accepted")
+    # the rule changes what is carried, nothing inside the window
+    assert np.array_equal(Ytil_a, Ytil_b) and np.array_equal(res_a.adv, res_b.adv)
+    assert np.array_equal(res_a.y_out, res_b.y_out)
+    rej, keep = res_b.rejected, ~res_b.rejected
+    assert rej.sum() > 50 and (rej & (res_b.adv == 1)).sum() > 5 and (rej & (res_b.adv > 1)).sum() > 5
+    assert np.array_equal(next_a[keep], next_b[keep])
+    for b in np.nonzero(rej)[0]:
+        j = int(res_b.adv[b])                                        # rejected position: state j-1 is the last kept one
+        state = y[b] if j == 1 else Ytil_b[b, j - 2]
+        want = den(state[None], np.array([n[b] + j - 1]))[0]
+        assert np.allclose(next_b[b], want, atol=1e-14)
+        assert not np.allclose(next_b[b], next_a[b], atol=1e-9) or n[b] + j >= 12
+    with pytest.raises(ValueError):
+        S.window_efficient(sched, den, y, n, ids, stale, K, seed=8, carry="previous")
+
+
+def test_efficient_frozen_last_accepted_sampler_is_exact_in_law():
+    B, K = 40_000, 6
+    sched, den = _ring()
+    seq = S.sequential_chain(sched, den, B, 2, seed=111)
+    spec, st = S.sample_efficient(sched, den, B, 2, K, seed=333, carry="last_accepted")
+    assert st.steps == B * sched.T and st.target_calls == st.windows + 1
+    assert 0.3 < st.rejections / st.chain_windows < 0.95
+    radius = lambda v: np.linalg.norm(v, axis=1)
+    for f in (lambda v: v[:, 0], lambda v: v[:, 1], radius, lambda v: np.arctan2(v[:, 1], v[:, 0])):
+        assert stats.ks_2samp(f(spec), f(seq)).pvalue > 1e-4
+    const = lambda v, k: np.full_like(np.asarray(v, dtype=np.float64), 0.7)
+    sched19 = W.cosine_schedule(19)
+    out, st2 = S.sample_efficient(sched19, const, 30, 3, 4, seed=2, carry="last_accepted")
+    assert np.array_equal(out, S.sequential_chain(sched19, const, 30, 3, seed=2)) and st2.rejections == 0
