@@ -174,7 +174,7 @@ def run_gpu(cfg, steps, warmup, stages, drafter="frozen", loop="eager", wps=1, v
     else:
         k_ms, k_launches, _ = timed[plan["stage"]]
     cw = list(counters_roof)
-    if drafter == "efficient_frozen" and "den_which" in plan:
+    if drafter.startswith("efficient_frozen") and "den_which" in plan:
         # one call per window on the start state and all drafts but a chain's final state:
         # rows = chain-windows + sum Kt - chains finished; expressed through the counters the plan uses
         cw[4] = cw[4] + 2 * cw[1] - cfg.B * (steps if events_in_loop else 1)
@@ -237,8 +237,8 @@ def run_context(cfg, drafter="frozen"):
         B = int(b.B_active.item())
         windows += 1
     rate = (accepted.double() / reached.clamp(min=1).double()).tolist()
-    calls = windows * (2 if (cfg.kind not in ("langevin", "phi4") and K > 1 and drafter != "efficient_frozen") else 1)
-    calls += 1 if drafter == "efficient_frozen" else 0
+    calls = windows * (2 if (cfg.kind not in ("langevin", "phi4") and K > 1 and not drafter.startswith("efficient_frozen")) else 1)
+    calls += 1 if drafter.startswith("efficient_frozen") else 0
     out = {"acceptance_rate_by_position": [round(x, 4) for x in rate],
            "target_calls_per_pass": calls, "chain_steps_per_target_call": round(T / calls, 3)}
     del smp
@@ -308,10 +308,11 @@ def _oracle_share(job):
             y = philox.initial_state(seed, ids, cfg.d)
             n = np.zeros(nchains, dtype=np.int64)
             runs += 1
-            Dfz = D(y, n) if drafter == "efficient_frozen" else None
+            Dfz = D(y, n) if drafter.startswith("efficient_frozen") else None
             while n.size and time.perf_counter() - t0 < budget_s:
-                if drafter == "efficient_frozen":
-                    res, _, _, _, Dnext = S.window_efficient(sched, D, y, n, ids, Dfz, cfg.K, seed)
+                if drafter.startswith("efficient_frozen"):
+                    res, _, _, _, Dnext = S.window_efficient(sched, D, y, n, ids, Dfz, cfg.K, seed,
+                                                             carry="last_accepted" if drafter.endswith("last_accepted") else "draft")
                     y_out, adv = res.y_out, res.adv
                     Dfz = Dnext[n + adv < cfg.T]
                 elif cfg.kind in ("langevin", "phi4"):
@@ -546,10 +547,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(DESCRIPTIONS))
     ap.add_argument("--stages", action="store_true", help="time every stage (adds event overhead)")
-    ap.add_argument("--drafter", default="frozen", choices=["frozen", "independent", "efficient_frozen"],
+    ap.add_argument("--drafter", default="frozen", choices=["frozen", "independent", "efficient_frozen", "efficient_frozen_last_accepted"],
                     help="frozen (default, the benchmark's drafter); independent: a cheaper network of the same "
                          "family called at every window position; efficient_frozen: frozen on the prediction "
-                         "carried over from the previous window, one batched target call per window (c1-c4)")
+                         "carried over from the previous window, one batched target call per window (c1-c4); "
+                         "efficient_frozen_last_accepted: the same with the appendix's alternative carry rule "
+                         "(after a rejection, the prediction at the last accepted state)")
     ap.add_argument("--loop", default=None, choices=["eager", "multi", "graph", "fused"],
                     help="window loop: eager = one host readback of the batch size per window; multi = batch size kept "
                          "on the device, --windows-per-sync windows per readback; graph = multi with window + advance "

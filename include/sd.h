@@ -96,6 +96,16 @@ int sd_set_draft_mode(sd_ctx* ctx, int mode);           /* SD_DRAFT_FROZEN (defa
  * sd_set_carry (both dev, D_frozen must not alias Dq_ext; NULL, NULL unregisters).  The caller
  * initialises D_frozen with the target's prediction at the initial states. */
 int sd_set_carry(sd_ctx* ctx, const float* Dq_ext, float* D_frozen);
+/* Which prediction sd_advance carries (App. on extending the draft models, last sentence of the
+ * paragraph on the efficient frozen draft strategy): SD_CARRY_DRAFT (default) = Dq_ext[b][adv[b]], the
+ * prediction at the draft state of the position the chain advanced to; SD_CARRY_LAST_ACCEPTED = after
+ * a rejection Dq_ext[b][adv[b]-1] instead, the prediction at the last state the chain kept (row 0,
+ * the window's own start state, when the first draft was rejected), at that state's step index;
+ * chains without a rejection carry the same row under both rules.  With SD_CARRY_LAST_ACCEPTED
+ * sd_advance needs its `rejected` argument (SD_ERR_ARG when it is NULL).  Errors: SD_ERR_ARG. */
+#define SD_CARRY_DRAFT 0
+#define SD_CARRY_LAST_ACCEPTED 1
+int sd_set_carry_rule(sd_ctx* ctx, int32_t rule);
 /* Temperature tau > 0 of the accept test (App. "Influence of the temperature"); 1 = exact.       */
 int sd_set_temperature(sd_ctx* ctx, float tau);
 /* Measurement aid: launch shape of the accept / reflect kernel for rows of more than 256 16-byte

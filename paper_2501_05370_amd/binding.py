@@ -23,6 +23,8 @@ SD_DRAFT_EXPLICIT = 1
 SD_DRAFT_FROZEN_REUSED = 2
 SD_MAX_WINDOW = 64
 SD_STATIC_MAX_CHAINS = 65536
+SD_CARRY_DRAFT = 0
+SD_CARRY_LAST_ACCEPTED = 1
 
 
 class SDError(RuntimeError):
@@ -50,6 +52,7 @@ _SIGNATURES = {
     "sd_draft_step": (c_int, [c_void_p, c_int32, c_int32] + [c_void_p] * 10),
     "sd_set_start_prediction": (c_int, [c_void_p, c_void_p]),
     "sd_set_carry": (c_int, [c_void_p, c_void_p, c_void_p]),
+    "sd_set_carry_rule": (c_int, [c_void_p, c_int32]),
     "sd_set_draft_mirror": (c_int, [c_void_p, c_void_p]),
     "sdden_eval_mirror": (c_int, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "sd_verify": (c_int, [c_void_p, c_int32] + [c_void_p] * 12),
@@ -197,6 +200,9 @@ class Context:
         self._keep_carry = (Dq_ext, D_frozen)
         self._check(self._lib.sd_set_carry(self._h, _dev(Dq_ext, torch.float32, "Dq_ext", True),
                                            _dev(D_frozen, torch.float32, "D_frozen", True)), "sd_set_carry")
+
+    def sd_set_carry_rule(self, rule: int):
+        self._check(self._lib.sd_set_carry_rule(self._h, int(rule)), "sd_set_carry_rule")
 
     def sd_workspace_bytes(self, Bmax: int) -> int:
         return int(self._lib.sd_workspace_bytes(self._h, Bmax))

@@ -23,6 +23,7 @@ struct sd_ctx {
   const int32_t* active = nullptr;
   const float* carry_src = nullptr;    // FROZEN_REUSED: predictions [B,K+1,d] of the window just verified
   float* carry_dst = nullptr;          //   and the [B,d] frozen predictions sd_advance fills for the next one
+  int carry_rule = 0;                  // SD_CARRY_DRAFT / SD_CARRY_LAST_ACCEPTED
   uint16_t* draft_mirror = nullptr;    // optional bf16 image of the drafted rows, same layout as Ytilde
   const float* start_pred = nullptr;   // EXPLICIT mode: D(y_n, n) as [B,d], replaces row 0 of Dq
   void* ws = nullptr;

@@ -688,7 +688,8 @@ __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __res
                                                               int Bprev, int d, int chunks,
                                                               const float* __restrict__ carry_src,
                                                               float* __restrict__ carry_dst,
-                                                              const int32_t* __restrict__ adv, int rs) {
+                                                              const int32_t* __restrict__ adv, int rs,
+                                                              const uint8_t* __restrict__ carry_rej) {
   // Bprev = number of chains that entered the window (host bound; rows beyond the device-side count carry
   // rank -2 and are skipped).  chunks > 0: a row takes `chunks` workgroups; chunks < 0: a workgroup takes
   // -chunks whole rows.
@@ -730,9 +731,11 @@ __global__ __launch_bounds__(kBlock) void advance_move_kernel(const float* __res
     v.load(src + static_cast<int64_t>(col) * VEC);
     v.store(dst + static_cast<int64_t>(col) * VEC);
     if (carry_src && dpos >= 0) {
-      // the surviving chain also takes along the target's prediction at the draft state of the
-      // position it advanced to: next window's frozen vector
-      v.load(carry_src + (static_cast<int64_t>(b) * rs + adv[b]) * d + static_cast<int64_t>(col) * VEC);
+      // the surviving chain also takes along the next window's frozen vector: the target's prediction at the
+      // draft state of the position it advanced to, or (carry_rej given) after a rejection the one at the last
+      // state it kept, one row earlier
+      const int row = adv[b] - (carry_rej && carry_rej[b] ? 1 : 0);
+      v.load(carry_src + (static_cast<int64_t>(b) * rs + row) * d + static_cast<int64_t>(col) * VEC);
       v.store(carry_dst + static_cast<int64_t>(dpos) * d + static_cast<int64_t>(col) * VEC);
     }
   }
@@ -877,6 +880,14 @@ int sd_set_carry(sd_ctx* ctx, const float* Dq_ext, float* D_frozen) {
   return SD_OK;
 }
 
+int sd_set_carry_rule(sd_ctx* ctx, int32_t rule) {
+  if (!ctx) return SD_ERR_ARG;
+  if (rule != SD_CARRY_DRAFT && rule != SD_CARRY_LAST_ACCEPTED)
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_set_carry_rule: rule must be SD_CARRY_DRAFT or SD_CARRY_LAST_ACCEPTED");
+  ctx->carry_rule = rule;
+  return SD_OK;
+}
+
 int sd_set_draft_mirror(sd_ctx* ctx, uint16_t* Ytilde_bf16) {
   if (!ctx) return SD_ERR_ARG;
   ctx->draft_mirror = Ytilde_bf16;
@@ -1018,6 +1029,8 @@ int sd_verify(sd_ctx* ctx, int32_t B, const float* y, const int32_t* n, const in
 static int advance_impl(sd_ctx* ctx, void* ws, int32_t B, const float* y_out, const int32_t* adv,
                         const uint8_t* rejected, float* y, int32_t* n, int64_t* chain_id, float* out,
                         int32_t* B_active, int64_t* counters, hipStream_t st) {
+  if (ctx->mode == SD_DRAFT_FROZEN_REUSED && ctx->carry_src && ctx->carry_rule == SD_CARRY_LAST_ACCEPTED && !rejected)
+    return sdi::fail(ctx->err, SD_ERR_ARG, "sd_advance: the last-accepted carry rule needs the `rejected` array");
   if (B == 0) {
     hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, st, B_active, 0);
     SD_HIP_TRY(ctx->err, hipGetLastError());
@@ -1041,12 +1054,13 @@ static int advance_impl(sd_ctx* ctx, void* ws, int32_t B, const float* y_out, co
                                          : static_cast<int64_t>(B) * chunks;
     if (grid > 0x7fffffffLL) return sdi::fail(ctx->err, SD_ERR_UNSUPPORTED, "sd_advance: B*d too large");
     const float* csrc = ctx->mode == SD_DRAFT_FROZEN_REUSED ? ctx->carry_src : nullptr;
+    const uint8_t* crej = csrc && ctx->carry_rule == SD_CARRY_LAST_ACCEPTED ? rejected : nullptr;
     if (vec) hipLaunchKernelGGL(advance_move_kernel<4>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
                                 y_out, rank, n_new, id_all, totals, y, n, chain_id, out, B_active, B, ctx->d, chunks,
-                                csrc, ctx->carry_dst, adv, ctx->K + 1);
+                                csrc, ctx->carry_dst, adv, ctx->K + 1, crej);
     else     hipLaunchKernelGGL(advance_move_kernel<1>, dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, st,
                                 y_out, rank, n_new, id_all, totals, y, n, chain_id, out, B_active, B, ctx->d, chunks,
-                                csrc, ctx->carry_dst, adv, ctx->K + 1);
+                                csrc, ctx->carry_dst, adv, ctx->K + 1, crej);
   }
   SD_HIP_TRY(ctx->err, hipGetLastError());
   return SD_OK;

@@ -40,10 +40,11 @@ def make_sampler(cfg, B=None, out_rows=None, seed=None, drafter: str = "frozen",
         den = make_denoiser(cfg, B * cfg.K)
         draft = make_denoiser(cfg, B, draft_params)
         return IndependentDrafterSampler(ctx, den, draft, B, out_rows)
-    if drafter == "efficient_frozen":
+    if drafter in ("efficient_frozen", "efficient_frozen_last_accepted"):
         if cfg.kind == "langevin":
             raise ValueError("the efficient frozen drafter needs a diffusion workload")
-        return EfficientFrozenSampler(ctx, make_denoiser(cfg, B * (cfg.K + 1)), B, out_rows)
+        carry = "last_accepted" if drafter.endswith("last_accepted") else "draft"
+        return EfficientFrozenSampler(ctx, make_denoiser(cfg, B * (cfg.K + 1)), B, out_rows, carry=carry)
     if drafter != "frozen":
         raise ValueError(drafter)
     if cfg.kind == "langevin":

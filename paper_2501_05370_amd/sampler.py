@@ -243,10 +243,15 @@ class IndependentDrafterSampler(_SamplerBase):
 class EfficientFrozenSampler(_SamplerBase):
     """The efficient frozen drafter: the draft mean freezes the target's prediction at the previous
     window's draft state, carried through ``sd_advance``; one batched target call per window on the
-    start state and all drafts (``sd_draft`` -> ``sdden_eval`` -> ``sd_verify`` -> ``sd_advance``)."""
+    start state and all drafts (``sd_draft`` -> ``sdden_eval`` -> ``sd_verify`` -> ``sd_advance``).
+    carry: "draft" (the prediction at the draft state of the position advanced to) or "last_accepted" (after a
+    rejection, the prediction at the last state the chain kept): the two rules of ``sd_set_carry_rule``."""
 
-    def __init__(self, ctx: Context, den: Denoiser, B: int, out_rows: Optional[int] = None):
-        from .binding import SD_DRAFT_FROZEN_REUSED
+    def __init__(self, ctx: Context, den: Denoiser, B: int, out_rows: Optional[int] = None, carry: str = "draft"):
+        from .binding import SD_CARRY_DRAFT, SD_CARRY_LAST_ACCEPTED, SD_DRAFT_FROZEN_REUSED
+        rules = {"draft": SD_CARRY_DRAFT, "last_accepted": SD_CARRY_LAST_ACCEPTED}
+        if carry not in rules:
+            raise ValueError(f"carry must be one of {sorted(rules)}")
         self.den = den
         self._setup(ctx, B, out_rows, False)
         b, K, d, f32 = self.buf, ctx.K, ctx.d, dict(dtype=torch.float32, device="cuda")
@@ -256,6 +261,7 @@ class EfficientFrozenSampler(_SamplerBase):
         b.Dq_ext = torch.zeros(B, K + 1, d, **f32)
         ctx.sd_set_draft_mode(SD_DRAFT_FROZEN_REUSED)
         ctx.sd_set_carry(b.Dq_ext, b.Dfz)
+        ctx.sd_set_carry_rule(rules[carry])
         # bf16 image of the window rows for denoisers whose first GEMM reads bf16 (written by sd_draft)
         self.mirror = (torch.zeros(B, K + 1, d, dtype=torch.int16, device="cuda")
                        if getattr(den, "wants_bf16", False) else None)

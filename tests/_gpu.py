@@ -74,7 +74,7 @@ def gpu_chain_stepper(cfg, drafter="frozen", draft_params=None, tau=None, seed=N
     if tau is not None:
         smp.ctx.sd_set_temperature(tau)
     b = smp.buf
-    eff = drafter == "efficient_frozen"
+    eff = drafter.startswith("efficient_frozen")
 
     def start(cid):
         smp.start(torch.tensor([cid], dtype=torch.int64, device="cuda"))
