@@ -17,6 +17,10 @@
 // product (N = rank, long K) has few output tiles: its K range is split over gridDim.y and the
 // partial sums go to separate slabs that a second small kernel adds in a fixed order (no atomics:
 // results do not depend on scheduling).
+// The Bt fragment is the FIRST MFMA operand: the accumulator tile is then C^T, a lane owns one row m of C and,
+// per 32x32 tile, four runs of 4 consecutive columns, so everything the epilogues move (partial slabs, the X
+// tile, the output) goes as 16-byte accesses, 16 per thread instead of 64 four-byte ones.  The second product
+// has K = rank: its K loop is as short as its prologue and epilogue, and those are what its speed hangs on.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -30,6 +34,12 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 32;
 
+struct __attribute__((aligned(16))) RowInfo {
+  int32_t src;
+  float gp, cf;
+  int32_t pad;
+};
+
 struct Args {
   const float* A;          // rows of lda floats; tile row r reads row arow[r] (or r when arow is null)
   const int32_t* arow;
@@ -41,12 +51,12 @@ struct Args {
   // stage 1: partial sums, slab s = part + s * slab_stride, dense rows of N floats
   float* part;
   int64_t slab_stride;
-  // stage 2 epilogue: out[src] = acc + gperp[k] X[src] + coef[k] mu,  src = rowidx[gm], k = krow[src]
-  const int32_t* rowidx;
-  const int32_t* krow;
+  // stage 2 epilogue: out[src] = acc + gp X[src] + cf mu with (src, gp, cf) = rowinfo[gm], which
+  // reduce_gain_kernel fills: src = rowidx[gm], gp = gperp[krow[src]], cf = coef[krow[src]]
+  const RowInfo* rowinfo;
   const float* X;
   float* out;
-  const float *gperp, *coef, *mu;
+  const float* mu;
 };
 
 template <int N>
@@ -125,38 +135,33 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
     if (k < nk) LRGEMM_FETCH(k, k);
 
   // STAGE 2: everything the epilogue needs from memory is requested here, while the first slices are on
-  // their way: the tile's source rows and per-row scalars go through LDS (one row per thread), then each
-  // thread requests its 64 elements of X.  Left to the epilogue, the chain rowidx -> krow -> gperp -> X
-  // costs four dependent round trips per 32-row group, as much as the short K loop (K = rank) itself.
-  __shared__ int sh_src[STAGE == 2 ? BM : 1];
-  __shared__ float sh_gp[STAGE == 2 ? BM : 1], sh_cf[STAGE == 2 ? BM : 1];
-  float xv[STAGE == 2 ? TM : 1][16][TN];
-  float muv[TN];
+  // their way: a lane's two rows of the tile (source row and per-row scalars, one 16-byte record each), then
+  // its 64 elements of X as 16 16-byte loads.  Left to the epilogue these are dependent round trips per row
+  // group, as much as the short K loop (K = rank) itself.
+  f32x4 xv[STAGE == 2 ? TM : 1][TN][4];
+  f32x4 muv[STAGE == 2 ? TN : 1][4];
+  int rsrc[TM];
+  float rgp[TM], rcf[TM];
   if (STAGE == 2) {
-    if (t < BM) {
-      const int gm = tile_m * BM + t;
-      const int src = p.rowidx[gm < M ? gm : M - 1];
-      const int k = p.krow[src];
-      sh_src[t] = gm < M ? src : -1;
-      sh_gp[t] = p.gperp[k];
-      sh_cf[t] = p.coef[k];
-    }
-    __syncthreads();
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
-      muv[j] = gn < p.N ? p.mu[gn] : 0.f;
+    for (int i = 0; i < TM; ++i) {
+      const int gm = tile_m * BM + wm * (BM / WM) + i * 32 + l32;
+      const RowInfo info = p.rowinfo[gm < M ? gm : M - 1];
+      rsrc[i] = gm < M ? info.src : -1;
+      rgp[i] = info.gp;
+      rcf[i] = info.cf;
     }
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int src = sh_src[wm * (BM / WM) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3)];
+      for (int q = 0; q < 4; ++q) {
+        const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + q * 8 + half * 4;
+        muv[j][q] = gn < p.N ? *reinterpret_cast<const f32x4*>(p.mu + gn) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
-          xv[i][v][j] = (src >= 0 && gn < p.N) ? p.X[static_cast<int64_t>(src) * p.N + gn] : 0.f;
-        }
+        for (int i = 0; i < TM; ++i)
+          xv[i][j][q] = (rsrc[i] >= 0 && gn < p.N)
+                            ? *reinterpret_cast<const f32x4*>(p.X + static_cast<int64_t>(rsrc[i]) * p.N + gn)
+                            : f32x4{0.f, 0.f, 0.f, 0.f};
       }
   }
 
@@ -190,58 +195,65 @@ __global__ __launch_bounds__(64 * WM * WN) void kernel(Args p) {
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][e], b[j][e], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j][e], a[i][e], acc[i][j], 0, 0, 0);
     }
   }
 #undef LRGEMM_FETCH
 
-  // acc[i][j][v] is element (row = (v/4)*8 + half*4 + v%4, col = l32) of its 32x32 tile
+  // acc[i][j][4q + e] is element (row m = l32, column n = 8q + 4 half + e) of its 32x32 tile of C
+  if (STAGE == 1) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i) {
+      const int gm = tile_m * BM + wm * (BM / WM) + i * 32 + l32;
+      if (gm >= M) continue;
+      float* dst = p.part + static_cast<int64_t>(blockIdx.y) * p.slab_stride + static_cast<int64_t>(gm) * p.N;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int gm = tile_m * BM + wm * (BM / WM) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-      if (STAGE != 1 || gm >= M) continue;
-      {
-        float* dst = p.part + static_cast<int64_t>(blockIdx.y) * p.slab_stride + static_cast<int64_t>(gm) * p.N;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
-          if (gn < p.N) dst[gn] = acc[i][j][v];
+        for (int q = 0; q < 4; ++q) {
+          const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + q * 8 + half * 4;
+          if (gn < p.N)
+            *reinterpret_cast<f32x4*>(dst + gn) =
+                f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
         }
-      }
     }
   }
   if (STAGE == 2) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      if (rsrc[i] < 0) continue;
+      float* dst = p.out + static_cast<int64_t>(rsrc[i]) * p.N;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = wm * (BM / WM) + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-        const int src = sh_src[row];
-        if (src < 0) continue;
-        const float gp = sh_gp[row], cf = sh_cf[row];
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + l32;
-          if (gn < p.N) p.out[static_cast<int64_t>(src) * p.N + gn] = acc[i][j][v] + gp * xv[i][v][j] + cf * muv[j];
+        for (int q = 0; q < 4; ++q) {
+          const int gn = tile_n * BN + wn * (BN / WN) + j * 32 + q * 8 + half * 4;
+          if (gn >= p.N) continue;
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = acc[i][j][4 * q + e] + rgp[i] * xv[i][j][q][e] + rcf[i] * muv[j][q][e];
+          *reinterpret_cast<f32x4*>(dst + gn) = o;
         }
-      }
+    }
   }
 }
 
-// P'[gm][a] = gain[k][a] * (sum_s part_s[gm][a] - sab[k] qmu[a]),  k = krow[rowidx[gm]]; slabs added in order
+// P'[gm][a] = gain[k][a] * (sum_s part_s[gm][a] - sab[k] qmu[a]),  k = krow[rowidx[gm]]; slabs added in order.
+// Also leaves the per-row record of the second product's epilogue (source row, gperp[k], coef[k]).
 __global__ __launch_bounds__(256) void reduce_gain_kernel(const float* __restrict__ part, int64_t slab_stride, int nsplit,
                                                           const int32_t* __restrict__ count, const int32_t* __restrict__ rowidx,
                                                           const int32_t* __restrict__ krow, const float* __restrict__ gain,
                                                           const float* __restrict__ sab, const float* __restrict__ qmu,
-                                                          float* __restrict__ P, int N) {
+                                                          float* __restrict__ P, int N, const float* __restrict__ gperp,
+                                                          const float* __restrict__ coef, RowInfo* __restrict__ rowinfo) {
   const int M = *count;
   const int n4 = N / 4;
   const int64_t g = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (g >= static_cast<int64_t>(M) * n4) return;
   const int gm = static_cast<int>(g / n4), c = static_cast<int>(g % n4) * 4;
-  const int k = krow[rowidx[gm]];
+  const int src = rowidx[gm];
+  const int k = krow[src];
+  if (c == 0) rowinfo[gm] = RowInfo{src, gperp[k], coef[k], 0};
   const int64_t o = static_cast<int64_t>(gm) * N + c;
   float4 s = *reinterpret_cast<const float4*>(part + o);
   for (int i = 1; i < nsplit; ++i) {
