@@ -405,7 +405,8 @@ def kernel_gemm(iters=20, rows_per_chain_masked=1, variants=None):
 def kernel_verify(workload, accept, shapes, iters=20):
     """The accept / first-reject / reflect kernel alone, at the batch size of a workload, on inputs whose first
     rejection is planted: `all` = every draft accepted (prediction rows equal the window-start prediction, so
-    Delta = 0), `second` = every chain rejects its second draft, `mixed` = the first rejection of a chain is
+    Delta = 0), `second` = every chain rejects its second draft, `tail` = the same except that one chain in 32 accepts
+    everything (the launch then lasts as long as a lone chain's dependent steps), `mixed` = the first rejection of a chain is
     geometric with per-position acceptance 0.55 (the shape the c4 sampler shows after its first windows).  Reports,
     per launch shape, the mean launch time and the rate of the bytes the method needs (rows up to the first
     rejection, the four rows of the reflection, the state written) and of the rows the group schedule streams."""
@@ -427,6 +428,9 @@ def kernel_verify(workload, accept, shapes, iters=20):
         jr = torch.full((B,), K, dtype=torch.int64)                    # K = no rejection
     elif accept == "second":
         jr = torch.ones(B, dtype=torch.int64)
+    elif accept == "tail":
+        jr = torch.ones(B, dtype=torch.int64)
+        jr[::32] = K                                                   # one chain in 32 accepts every draft
     else:
         rng = np.random.default_rng(0)
         jr = torch.as_tensor(np.minimum(K, 1 + rng.geometric(0.45, size=B) - 1 + 0), dtype=torch.int64)
@@ -567,7 +571,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the untimed extras (acceptance by position, sequential chain on the GPU)")
-    ap.add_argument("--accept", default="mixed", choices=["all", "second", "mixed"], help="with --kernel verify")
+    ap.add_argument("--accept", default="mixed", choices=["all", "second", "tail", "mixed"], help="with --kernel verify")
     ap.add_argument("--shapes", default="0", help="with --kernel verify: comma-separated sd_set_verify_shape codes")
     ap.add_argument("--kernel", default=None, choices=["gemm", "verify", "draft", "stream", "mfma"],
                     help="time one kernel family in isolation instead of the sampler (controlled runs behind the "
