@@ -61,8 +61,8 @@ typedef enum {
 #define SD_DRAFT_EXPLICIT 1       /* caller supplies the draft means mp[B,K,d] (any drafter)       */
 #define SD_DRAFT_FROZEN_REUSED 2 /* frozen on a prediction carried over from the previous window:
                                     D(y~_n, n) at the DRAFT state of position n, which that window's
-                                    verification already computed ("efficient frozen draft strategy",
-                                    App. on extending the draft models).  One batched target call per
+                                    verification already computed (the efficient frozen draft strategy
+                                    of the App. on extending the draft models).  One batched target call per
                                     window; window arrays hold K+1 rows per chain, see below.      */
 
 typedef struct sd_ctx sd_ctx;     /* opaque; owns only its device copy of the schedule            */

@@ -1,7 +1,7 @@
 /* sdden.h -- C ABI of the target predictions D(y, k) used by the synthetic workloads.
  *
- * The method treats the target's drift as a black-box network ("b_t is approximated using a
- * neural network", Sec. 3.1) that is evaluated on all drafted states of a window in one batched
+ * The method treats the target's drift as a black-box network (Sec. 3.1: the drift is given by a
+ * trained network) that is evaluated on all drafted states of a window in one batched
  * call (Alg. "Speculative Sampling for DDM", the (Par.) line).  These are the stand-ins with a
  * plain definition; each maps rows X [R,d] with a per-row chain step krow [R] to out [R,d]:
  *

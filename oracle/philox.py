@@ -1,7 +1,7 @@
 """ORACLE (test infrastructure only) -- counter-based random streams of the chains.
 
-The paper only says "sample Z ~ N(0, Id)" and "sample U ~ Unif[0,1]" (detailed algorithm of
-speculative sampling for DDMs, App. "Detailed implementation").  So that the CPU oracle and the
+The paper asks for standard normal vectors Z and uniforms U on [0,1] and names no generator
+(detailed algorithm of speculative sampling for DDMs, App. "Detailed implementation").  So that the CPU oracle and the
 GPU library consume the *same* random numbers, both implement -- independently -- the published
 Philox4x32-10 generator (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as
 1, 2, 3", SC'11) keyed by absolute coordinates:
