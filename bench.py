@@ -70,7 +70,7 @@ def roofline_plan(cfg):
                     work=lambda c: 2.0 * (c[4] - c[1]) * d * H)
     if cfg.kind == "lowrank":
         rpad = -(-cfg.params.U.shape[1] // 16) * 16
-        return dict(kernel="lrgemm::kernel<128,128,2,2,STAGE=2,NS=2> (P' Q^T + epilogue, fp32 MFMA) of the batched target call", den_which=2,
+        return dict(kernel="lrgemm::kernel<64,128,1,4,STAGE=2,NS=2> (P' Q^T + epilogue, fp32 MFMA) of the batched target call", den_which=2,
                     den_min_rows=cfg.B + 1, bound="mfma", peak="mfma_fp32", scale=1e-12,
                     work=lambda c: 2.0 * (c[4] - c[1]) * d * rpad)
     if cfg.kind == "gmm":

@@ -300,7 +300,7 @@ int LowRankDenoiser::eval_ring(int R, const float* X, const int32_t* krow, float
   b.A = P; b.arow = nullptr; b.lda = rpad; b.Bt = Q; b.ldb = rpad; b.N = d; b.Kdim = rpad; b.count = count;
   b.rowinfo = rowinfo; b.X = X; b.out = out; b.mu = mu;
   prof.mark(2, st);
-  SD_HIP_TRY(err, (lrgemm::launch<128, 128, 2, 2, 2, 2>(b, R, 1, st)));
+  SD_HIP_TRY(err, (lrgemm::launch<64, 128, 1, 4, 2, 2>(b, R, 1, st)));
   prof.mark(2, st);
   SD_HIP_TRY(err, hipGetLastError());
   return SD_OK;
@@ -380,7 +380,7 @@ extern "C" int sdden_lowrank_create(int32_t d, int32_t r, const float* mu, const
       if (nk % ns == 0 && nk / ns >= 24) L->nsplit = ns;
   }
   hipError_t e = lrgemm::prepare<64, 128, 1, 4, 1, 2>();    // dynamic-LDS limits of the two GEMM stages
-  if (e == hipSuccess) e = lrgemm::prepare<128, 128, 2, 2, 2, 2>();
+  if (e == hipSuccess) e = lrgemm::prepare<64, 128, 1, 4, 2, 2>();
   if (e == hipSuccess) e = hipMalloc(&L->dev, h.size() * sizeof(float));
   if (e == hipSuccess) e = hipMemcpy(L->dev, h.data(), h.size() * sizeof(float), hipMemcpyHostToDevice);
   if (e != hipSuccess) {
