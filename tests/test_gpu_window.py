@@ -56,7 +56,8 @@ def test_init_state_matches_oracle_stream():
 
 
 @pytest.mark.parametrize("name,kw", [("c1", dict(B=64)), ("c2", dict(B=300)), ("c2", dict(B=70, d=50, K=5)),
-                                     ("c2", dict(B=33, d=1000, K=16, M=3)), ("c2", dict(B=9, d=4100, K=3, M=2))])
+                                     ("c2", dict(B=33, d=1000, K=16, M=3)), ("c2", dict(B=9, d=4100, K=3, M=2)),
+                                     ("c2", dict(B=7, d=260, K=64, M=2)), ("c2", dict(B=20, d=64, K=1))])
 def test_draft_matches_oracle(name, kw):
     cfg, den = _gmm_case(name, **kw)
     rng = np.random.default_rng(1)
@@ -100,6 +101,10 @@ def _verify_case(cfg, den, B, seed, rng, mode="frozen", tau=1.0, shrink=1.0):
     ("c2", dict(B=16, d=1203, K=5, M=2), "frozen", 1.0),     # d % 4 != 0: scalar loads
     ("c2", dict(B=200, d=64, K=8), "explicit", 1.0),
     ("c2", dict(B=20, d=2052, K=18, M=3), "explicit", 0.7),
+    ("c2", dict(B=12, d=300, K=64, M=2), "frozen", 1.0),     # the largest window the library takes
+    ("c2", dict(B=6, d=8192, K=64, M=2), "frozen", 1.0),     # the same with a workgroup of 512 threads per chain
+    ("c2", dict(B=40, d=64, K=1), "frozen", 1.0),            # a window of one position: the sequential chain
+    ("c2", dict(B=10, d=64, K=64, M=2), "explicit", 1.0),
 ])
 def test_verify_matches_oracle(name, kw, mode, tau):
     cfg, den = _gmm_case(name, **kw)
@@ -123,7 +128,8 @@ def test_verify_matches_oracle(name, kw, mode, tau):
     assert nbad == near
     same = g_adv == res.adv
     assert np.array_equal(g_rej[same].astype(bool), res.rejected[same])
-    assert res.rejected.mean() > 0.05 or name == "c1"      # the reflection branch is exercised
+    # the reflection branch is exercised (the only position of a frozen window of one is exact: nothing to reject)
+    assert res.rejected.mean() > 0.05 or name == "c1" or (cfg.K == 1 and mode == "frozen")
     assert rel_err(host(y_out)[same], res.y_out[same]) < TOL
     assert np.max(np.abs(host(lu) - res.logu)) < 1e-5
     assert np.max(np.abs(host(lr) - res.logratio) / np.maximum(1.0, np.abs(res.logratio))) < 1e-5
