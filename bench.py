@@ -489,10 +489,12 @@ def kernel_stream(iters=20):
     import torch
     from paper_2501_05370_amd import binding
     torch.cuda.set_device(0)
-    for nbytes in (512 * 16 * 12288 * 4, 1 << 30):
+    for nbytes in (512 * 16 * 12288 * 4, 49152 * 21845):         # the c4 window arrays (403 MB); 1 GiB in whole rows
         src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
-        for mode, name, moved in ((0, "copy", 2 * nbytes), (1, "read", nbytes), (2, "fill", nbytes)):
+        for mode, name, moved in ((0, "copy", 2 * nbytes), (1, "read", nbytes), (2, "fill", nbytes),
+                                  (3, "copy, row per workgroup", 2 * nbytes), (4, "read, row per workgroup", nbytes),
+                                  (5, "fill, row per workgroup", nbytes)):
             us = _time_launches(lambda: binding.sd_measure_stream(src, dst, nbytes, mode), iters)
             print(json.dumps({"kernel": "stream_kernel", "mode": name, "buffer_bytes": nbytes, "bytes_moved": moved,
                               "avg_launch_us": round(us, 2), "TB/s": round(moved / (us * 1e-6) * 1e-12, 3),

@@ -22,6 +22,9 @@ extern "C" {
  *   mode 0  dst[i] = src[i]                      (reads bytes, writes bytes)
  *   mode 1  sums src into 4 bytes per workgroup written to dst (dst needs 4 * 4096 bytes)   (reads bytes)
  *   mode 2  dst[i] = constant                    (writes bytes)
+ *   mode 3, 4, 5  the same three passes with the access pattern of the window kernels: a workgroup takes
+ *           whole rows of 49152 bytes (a 12288-wide fp32 row), row after row, and a thread requests all its
+ *           pieces of a row before it uses any (`bytes` a multiple of 49152)
  * workgroups = 0 picks 16 per compute unit. */
 int sd_measure_stream(const void* src, void* dst, size_t bytes, int32_t mode, int32_t workgroups, void* stream);
 

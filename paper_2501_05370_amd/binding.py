@@ -402,7 +402,8 @@ class Denoiser:
 
 
 def sd_measure_stream(src: Optional[torch.Tensor], dst: torch.Tensor, nbytes: int, mode: int, workgroups: int = 0):
-    """Measurement kernel (include/sd_measure.h): streaming copy (0), read (1) or fill (2) of nbytes."""
+    """Measurement kernel (include/sd_measure.h): streaming copy (0), read (1) or fill (2) of nbytes; 3, 4, 5 the
+    same with a workgroup walking whole 48 KiB rows."""
     lib = load_library()
     rc = lib.sd_measure_stream(None if src is None else src.data_ptr(), dst.data_ptr(), nbytes, mode, workgroups, _stream())
     if rc != 0:

@@ -55,6 +55,43 @@ __global__ __launch_bounds__(256) void stream_kernel(const float4* __restrict__ 
   }
 }
 
+// The same three passes with the access pattern of the window kernels: a workgroup takes whole rows of kRowBytes
+// (the 48 KiB of a 12288-wide fp32 row), row after row, each thread requesting all its 16-byte pieces of the row
+// before it uses any.
+constexpr int kRowBytes = 49152;
+template <int MODE>
+__global__ __launch_bounds__(256) void stream_rows_kernel(const float4* __restrict__ src, float4* __restrict__ dst, size_t nrows) {
+  constexpr int PER = kRowBytes / 16 / 256;        // 12 pieces per thread and row
+  float acc = 0.f;
+  for (size_t r = blockIdx.x; r < nrows; r += gridDim.x) {
+    const size_t base = r * (kRowBytes / 16) + threadIdx.x;
+    if (MODE == 2) {
+      const float4 v = make_float4(1.f, 2.f, 3.f, 4.f);
+#pragma unroll
+      for (int i = 0; i < PER; ++i) dst[base + i * 256] = v;
+    } else {
+      float4 v[PER];
+#pragma unroll
+      for (int i = 0; i < PER; ++i) v[i] = src[base + i * 256];
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        if (MODE == 0) dst[base + i * 256] = v[i];
+        else acc += v[i].x + v[i].y + v[i].z + v[i].w;
+      }
+    }
+  }
+  if (MODE == 1) {
+    __shared__ float sh[256];
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float t = 0.f;
+      for (int k = 0; k < 256; ++k) t += sh[k];
+      reinterpret_cast<float*>(dst)[blockIdx.x] = t;
+    }
+  }
+}
+
 template <int SHAPE>
 __global__ __launch_bounds__(512) void mfma_kernel(int iters, float* __restrict__ sink) {
   const int lane = threadIdx.x & 63;
@@ -101,6 +138,9 @@ __global__ __launch_bounds__(512) void mfma_kernel(int iters, float* __restrict_
 extern "C" {
 
 int sd_measure_stream(const void* src, void* dst, size_t bytes, int32_t mode, int32_t workgroups, void* stream) {
+  const bool by_rows = mode >= 3;
+  if (by_rows) mode -= 3;
+  if (by_rows && bytes % kRowBytes != 0) return SD_ERR_ARG;
   if (!dst || (mode != 2 && !src) || bytes == 0 || (bytes & 15u) || mode < 0 || mode > 2 || workgroups < 0 ||
       workgroups > 4096 || (reinterpret_cast<uintptr_t>(dst) & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u))
     return SD_ERR_ARG;
@@ -109,6 +149,13 @@ int sd_measure_stream(const void* src, void* dst, size_t bytes, int32_t mode, in
   hipStream_t st = static_cast<hipStream_t>(stream);
   const float4* s = static_cast<const float4*>(src);
   float4* d = static_cast<float4*>(dst);
+  if (by_rows) {
+    const size_t nrows = bytes / kRowBytes;
+    if (mode == 0) hipLaunchKernelGGL(stream_rows_kernel<0>, dim3(grid), dim3(256), 0, st, s, d, nrows);
+    else if (mode == 1) hipLaunchKernelGGL(stream_rows_kernel<1>, dim3(grid), dim3(256), 0, st, s, d, nrows);
+    else hipLaunchKernelGGL(stream_rows_kernel<2>, dim3(grid), dim3(256), 0, st, s, d, nrows);
+    return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
+  }
   if (mode == 0) hipLaunchKernelGGL(stream_kernel<0>, dim3(grid), dim3(256), 0, st, s, d, bytes / 16);
   else if (mode == 1) hipLaunchKernelGGL(stream_kernel<1>, dim3(grid), dim3(256), 0, st, s, d, bytes / 16);
   else hipLaunchKernelGGL(stream_kernel<2>, dim3(grid), dim3(256), 0, st, s, d, bytes / 16);
