@@ -44,7 +44,7 @@ DESCRIPTIONS = {
 # WRITE_SIZE counters, the factors being what the same counters read for a plain device copy), taken from
 # profiles/hbm_traffic_all_kernels_c4.md and _c3.md (mean over the launches of a pass); workloads without such a
 # counter run report null
-MEASURED_TRAFFIC_BYTES = {"c4": 1221.3e6, "c3": 296.3e6}
+MEASURED_TRAFFIC_BYTES = {"c4": 1225.1e6, "c3": 277.8e6}
 
 # published MI355X peaks used as roofline denominators
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "mfma_fp32": (157.3, "TFLOP/s"),
