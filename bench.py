@@ -378,8 +378,8 @@ def kernel_gemm(iters=20, rows_per_chain_masked=1, variants=None):
     flops = {1: 2.0 * rows * d * H, 2: 2.0 * rows * H * H, 3: 2.0 * rows * H * d}
     ref = None
     names = {0: "kernel_pp", 1: "kernel_hs", 2: "kernel_pp without fragment reads (timing only)",
-             3: "kernel_pp without direct loads (timing only)", 4: "kernel_pp, MFMAs and barriers only (timing only)"}
-    vs = [(v, names[v]) for v in (variants or [0, 1, 2, 3, 4])]
+             3: "kernel_pp without direct loads (timing only)", 4: "kernel_pp, MFMAs and barriers only (timing only)", 5: "kernel_pp without the B fragment reads (timing only)"}
+    vs = [(v, names[v]) for v in (variants or [0, 1, 2, 3, 4, 5])]
     for variant, name in vs:
         den.sdden_mlp_select_gemm(variant)
         for _ in range(2):

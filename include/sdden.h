@@ -84,7 +84,9 @@ int sdden_profile_collect(sdden* den, double* total_ms, int64_t* launches);
  * 0 = the default (alternating-phase kernel); 1 = the earlier hand-scheduled kernel, kept so that
  * the two can be timed side by side on the same data (results agree).  2, 3, 4 = the default
  * kernel with its fragment reads / its direct loads / both left out: TIMING ONLY, the results are
- * wrong -- they locate what bounds the kernel (4 = the MFMA and barrier schedule alone). */
+ * wrong -- they locate what bounds the kernel (4 = the MFMA and barrier schedule alone); 5 = the
+ * default kernel without the fragment reads of the weight tile only (a third of its LDS reads),
+ * TIMING ONLY as well. */
 int sdden_mlp_select_gemm(sdden* den, int32_t variant);
 
 int sdden_destroy(sdden* den);

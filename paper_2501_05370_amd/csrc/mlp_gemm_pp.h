@@ -47,7 +47,9 @@ namespace mlpgemm {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // DIAG (timing experiments only, results wrong): bit 0 = no fragment reads, bit 1 = no direct loads in the
-// steady-state loop; 3 leaves the MFMAs and barriers: what the schedule itself can reach on this chip
+// steady-state loop, bit 2 = no B fragment reads (a third of the LDS read traffic: what a layout that reads 128 KiB
+// instead of 192 KiB per slice could gain at best); 3 leaves the MFMAs and barriers: what the schedule itself can
+// reach on this chip
 template <int EPI, bool GATHER = false, int DIAG = 0, int PM = 4, int PN = 8>
 __global__ __launch_bounds__(512) void kernel_pp(Args p) {
   constexpr int BM = 256, BN = 256;
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(512) void kernel_pp(Args p) {
     MLPPP_VMWAIT(W0_);                                                                                   \
     MLPPP_PHASE_END();                                                                                   \
     MLPPP_COMPUTE(0, 0, X);                                                                              \
-    if (!(DIAG & 1)) MLPPP_READ_B(Y, s_, 1);                                                             \
+    if (!(DIAG & 5)) MLPPP_READ_B(Y, s_, 1);                                                             \
     if (LD_ && !(DIAG & 2)) MLPPP_LD_A0(s_, (k2_) * 64);                                                 \
     MLPPP_WAIT_B(Y);                                                                                     \
     MLPPP_VMWAIT(W1_);                                                                                   \
@@ -229,7 +231,7 @@ __global__ __launch_bounds__(512) void kernel_pp(Args p) {
     MLPPP_VMWAIT(W2_);                                                                                   \
     MLPPP_PHASE_END();                                                                                   \
     MLPPP_COMPUTE(1, 1, Y);                                                                              \
-    if (NX_ && !(DIAG & 1)) MLPPP_READ_B(Y, (s_) ^ 1, 0);                                                \
+    if (NX_ && !(DIAG & 5)) MLPPP_READ_B(Y, (s_) ^ 1, 0);                                                \
     if (LD_ && !(DIAG & 2)) MLPPP_LD_A1(s_, (k2_) * 64);                                                 \
     MLPPP_WAIT_B(Y);                                                                                     \
     MLPPP_VMWAIT(W3_);                                                                                   \

@@ -71,6 +71,7 @@ hipError_t prepare_gemms() {
   if (e == hipSuccess) e = mlpgemm::prepare_pp<EPI, GATHER, 1>();
   if (e == hipSuccess) e = mlpgemm::prepare_pp<EPI, GATHER, 2>();
   if (e == hipSuccess) e = mlpgemm::prepare_pp<EPI, GATHER, 3>();
+  if (e == hipSuccess) e = mlpgemm::prepare_pp<EPI, GATHER, 4>();
   return e;
 }
 
@@ -92,6 +93,7 @@ int launch_gemm(const mlpgemm::Args& a, int R, hipStream_t st, std::string& err,
     else if (variant == 2) e = mlpgemm::launch_pp<EPI, GATHER, 1>(a, R, st);
     else if (variant == 3) e = mlpgemm::launch_pp<EPI, GATHER, 2>(a, R, st);
     else if (variant == 4) e = mlpgemm::launch_pp<EPI, GATHER, 3>(a, R, st);
+    else if (variant == 5) e = mlpgemm::launch_pp<EPI, GATHER, 4>(a, R, st);
     else e = mlpgemm::launch_pp<EPI, GATHER>(a, R, st);
   }
   else if (t128 >= 512) e = mlpgemm::launch<128, 128, 2, 2, EPI, 2, GATHER>(a, R, st);
@@ -108,7 +110,7 @@ struct MlpDenoiser final : sdden {
   int32_t *rowidx = nullptr, *count = nullptr;
   uint16_t *Xb = nullptr, *H1 = nullptr, *H2 = nullptr;
   int cap_rows = 0;
-  int gemm_variant = 0;          // 0: kernel_pp; measurement only: 1 = kernel_hs, 2..4 = kernel_pp with pieces left out
+  int gemm_variant = 0;          // 0: kernel_pp; measurement only: 1 = kernel_hs, 2..5 = kernel_pp with pieces left out
 
   ~MlpDenoiser() override {
     for (void* q : {static_cast<void*>(W1t), static_cast<void*>(W2t), static_cast<void*>(W3t), static_cast<void*>(tb),
@@ -268,7 +270,7 @@ extern "C" int sdden_mlp_create(int32_t d, int32_t H, int32_t E, const uint16_t*
 extern "C" int sdden_mlp_select_gemm(sdden* den, int32_t variant) {
   MlpDenoiser* m = dynamic_cast<MlpDenoiser*>(den);
   if (!m) return SD_ERR_ARG;
-  if (variant < 0 || variant > 4) return sdi::fail(m->err, SD_ERR_ARG, "sdden_mlp_select_gemm: variant must be 0..4");
+  if (variant < 0 || variant > 5) return sdi::fail(m->err, SD_ERR_ARG, "sdden_mlp_select_gemm: variant must be 0..5");
   m->gemm_variant = variant;
   return SD_OK;
 }
